@@ -1,0 +1,481 @@
+"""Pins of the fp64 oracle against what the paper and the mathematics fix.
+
+None of these tests re-type an oracle formula: each compares the oracle with a
+published known answer, a closed form, a library routine, an invariant the
+paper states, an independent scalar-loop implementation, or brute-force Monte
+Carlo.  A plausible mistake anywhere in the oracle (dropped term, wrong sign
+or index, transposed operand) fails at least one of them.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy import integrate, stats
+
+from oracle import csd_oracle as O
+from paper_2411_11925_amd import synth as S
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ RNG ----
+def test_philox_known_answers():
+    """Philox-4x32-10 known-answer vectors published with the generator
+    (Salmon et al., SC'11; Random123 kat_vectors)."""
+    n = 0
+    for line in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")):
+        line = line.split("#")[0].split()
+        if not line:
+            continue
+        w = [int(x, 16) for x in line]
+        got = O.philox4x32_10([w[0]], [w[1]], [w[2]], [w[3]], w[4], w[5])
+        assert [int(g[0]) for g in got] == w[6:10]
+        n += 1
+    assert n == 3
+
+
+def test_uniform23_is_exact_and_open_interval():
+    x = np.array([0, 1, 511, 512, 0xFFFFFFFF, 0x80000000], dtype=np.uint32)
+    u = O.uniform23(x)
+    assert u.dtype == np.float32
+    exact = ((x >> 9).astype(np.float64) + 0.5) / 2.0 ** 23
+    assert np.array_equal(u.astype(np.float64), exact)
+    assert u.min() > 0.0 and u.max() < 1.0
+
+
+def test_normals_follow_box_muller_in_libm():
+    """The fp32 polynomial transform equals Box-Muller evaluated with libm in
+    fp64 on the same words, to fp32 accuracy."""
+    rng = np.random.default_rng(1)
+    xa = rng.integers(0, 2 ** 32, 200000, dtype=np.uint64).astype(np.uint32)
+    xb = rng.integers(0, 2 ** 32, 200000, dtype=np.uint64).astype(np.uint32)
+    # include the extremes of both words
+    xa[:4] = [0, 0xFFFFFFFF, 0x80000000, 0x7FFFFFFF]
+    xb[:4] = [0, 0xFFFFFFFF, 0x80000000, 0x7FFFFFFF]
+    n0, n1 = O.normal_pair_f32(xa, xb)
+    u1 = ((xa >> 9).astype(np.float64) + 0.5) / 2 ** 23
+    u2 = ((xb >> 9).astype(np.float64) + 0.5) / 2 ** 23
+    r = np.sqrt(-2.0 * np.log(u1))
+    assert np.max(np.abs(n0 - r * np.cos(2 * np.pi * u2))) < 4e-6
+    assert np.max(np.abs(n1 - r * np.sin(2 * np.pi * u2))) < 4e-6
+
+
+def test_normals_distribution_and_stream_layout():
+    rows = np.arange(100000, dtype=np.uint64)
+    n = O.normals(42, rows, 7, O.STREAM_TRAJ, 16)
+    assert abs(n.mean()) < 3e-3 and abs(n.var() - 1) < 5e-3
+    assert abs((n ** 4).mean() - 3) < 0.05
+    for d in (0, 1, 2, 3, 15):
+        assert stats.kstest(n[:, d], "norm").pvalue > 1e-3
+    # columns are uncorrelated, and distinct slots / streams / seeds / rows differ
+    c = np.corrcoef(n.T)
+    assert np.max(np.abs(c - np.eye(16))) < 0.02
+    assert not np.array_equal(n, O.normals(42, rows, 8, O.STREAM_TRAJ, 16))
+    assert not np.array_equal(n, O.normals(42, rows, 7, O.STREAM_RESAMPLE_N, 16))
+    assert not np.array_equal(n, O.normals(43, rows, 7, O.STREAM_TRAJ, 16))
+    # keyed by the global row: a shifted window reproduces the same rows
+    assert np.array_equal(n[100:200], O.normals(42, rows[100:200], 7, O.STREAM_TRAJ, 16))
+    # rows beyond 2^32 use the high counter word
+    big = np.array([5, 5 + 2 ** 32], dtype=np.uint64)
+    nb = O.normals(42, big, 7, O.STREAM_TRAJ, 16)
+    assert np.array_equal(nb[0], n[5]) and not np.array_equal(nb[0], nb[1])
+    u = O.uniforms(42, rows, 0, O.STREAM_ACCEPT_U)
+    assert stats.kstest(u, "uniform").pvalue > 1e-3
+
+
+# ------------------------------------------------------------- schedule ----
+@pytest.mark.parametrize("T", [10, 100, 1000])
+def test_schedule_closed_forms(T):
+    s = O.cosine_schedule(T)
+    f = lambda t: math.cos((t / T + 0.008) / 1.008 * math.pi / 2) ** 2
+    # before the clip bites, abar_t is the ratio f(t)/f(0) of the published schedule
+    for t in range(1, T):
+        if 1 - f(t) / f(t - 1) < 0.999:
+            assert s.abar[t] == pytest.approx(f(t) / f(0), rel=1e-12)
+    assert s.beta[T] == pytest.approx(0.999)          # f(T) = 0: clipped
+    assert np.all(np.diff(s.abar) < 0)
+    assert np.allclose(np.cumprod(s.alpha), s.abar, rtol=1e-13)
+    assert np.all(s.beta_tilde[1:] < s.beta[1:]) and s.beta_tilde[1] == 0
+    # posterior precision of q(x_{t-1}|x_t,x_0) = alpha_t/beta_t + 1/(1-abar_{t-1})
+    # (product of the two Gaussians in x_{t-1}), an independent route to beta_tilde
+    for t in range(2, T + 1):
+        prec = s.alpha[t] / s.beta[t] + 1.0 / (1.0 - s.abar[t - 1])
+        assert s.beta_tilde[t] == pytest.approx(1.0 / prec, rel=1e-9)
+    assert s.log_beta_tilde_clip[1] == s.log_beta_tilde_clip[2] == pytest.approx(math.log(s.beta_tilde[2]))
+
+
+def test_schedule_spot_values():
+    """beta_1 = 1 - f(1)/f(0) and beta~_2 worked by hand for T = 100 and 10."""
+    s = O.cosine_schedule(100)
+    assert s.beta[1] == pytest.approx(6.3128e-4, rel=1e-4)
+    assert s.beta[2] == pytest.approx(1.11694e-3, rel=1e-4)
+    assert s.beta_tilde[2] == pytest.approx(4.0349e-4, rel=1e-4)
+    assert 1 / math.sqrt(s.abar[100]) == pytest.approx(2029.2, rel=1e-4)
+    s = O.cosine_schedule(10)
+    assert s.beta[1] == pytest.approx(2.79073e-2, rel=1e-4)
+    assert s.beta_tilde[2] == pytest.approx(2.07991e-2, rel=1e-4)
+
+
+# ------------------------------------------------- Gaussian log-density ----
+def test_gaussian_logpdf_is_a_density_and_matches_scipy():
+    mu, lv, tau = 0.7, math.log(0.3 ** 2), 1.3
+    pdf = lambda x: math.exp(O.gaussian_logpdf(np.array([x]), np.array([mu]), np.array([lv]), tau))
+    total, _ = integrate.quad(pdf, mu - 12, mu + 12)
+    assert total == pytest.approx(1.0, abs=1e-9)
+    rng = np.random.default_rng(0)
+    x, m, l = rng.normal(size=(5, 16)), rng.normal(size=(5, 16)), rng.normal(size=(5, 16))
+    want = stats.norm.logpdf(x, loc=m, scale=tau * np.exp(0.5 * l)).sum(axis=-1)
+    assert np.allclose(O.gaussian_logpdf(x, m, l, tau), want, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------- transition mean ----
+def test_transition_mean_equals_ddpm_posterior_mean():
+    """eps-form of mu equals the posterior-mean form with x0_hat (DDPM)."""
+    s = O.cosine_schedule(100)
+    rng = np.random.default_rng(2)
+    x, eh, v = rng.normal(size=(3, 16)), rng.normal(size=(3, 16)), rng.normal(size=(3, 16))
+    for t in (2, 17, 60, 99):
+        mu, lv = O.transition_params(s, x, t, eh, v)
+        x0h = (x - math.sqrt(1 - s.abar[t]) * eh) / math.sqrt(s.abar[t])
+        want = (math.sqrt(s.abar[t - 1]) * s.beta[t] / (1 - s.abar[t]) * x0h
+                + math.sqrt(s.alpha[t]) * (1 - s.abar[t - 1]) / (1 - s.abar[t]) * x)
+        assert np.allclose(mu, want, rtol=1e-10, atol=1e-10)
+        # learned-range variance: v = +1 -> beta_t, v = -1 -> clipped posterior variance
+        _, lv1 = O.transition_params(s, x, t, eh, np.ones_like(v))
+        _, lv0 = O.transition_params(s, x, t, eh, -np.ones_like(v))
+        assert np.allclose(np.exp(lv1), s.beta[t]) and np.allclose(np.exp(lv0), s.beta_tilde[t])
+        assert np.all((lv >= np.minimum(lv0, lv1) - 5 * abs(lv1 - lv0)))
+
+
+# ------------------------------------------------------ the head forward ----
+def _scalar_head_forward(cfg, blob, sched, x, t, z):
+    """Independent scalar-loop implementation of the head definition (one row)."""
+    D, C, W, L = cfg.token_dim, cfg.cond_dim, cfg.width, cfg.n_blocks
+    pos = [0]
+
+    def take(n):
+        a = [float(v) for v in blob[pos[0]:pos[0] + n]]
+        pos[0] += n
+        return a
+
+    def lin(n_out, n_in):
+        w, b = take(n_out * n_in), take(n_out)
+        return lambda vec: [sum(w[o * n_in + i] * vec[i] for i in range(n_in)) + b[o]
+                            for o in range(n_out)]
+
+    sil = lambda a: a / (1.0 + math.exp(-a))
+
+    def ln(h):
+        m = sum(h) / len(h)
+        var = sum((a - m) ** 2 for a in h) / len(h)
+        return [(a - m) / math.sqrt(var + cfg.ln_eps) for a in h]
+
+    t1, t2, cond, inp = lin(W, 256), lin(W, W), lin(W, C), lin(W, D)
+    tv = (1000.0 / cfg.n_steps if cfg.t_scale is None else cfg.t_scale) * (t - 1)
+    feats = [math.cos(tv * 10000.0 ** (-i / 128)) for i in range(128)] + \
+            [math.sin(tv * 10000.0 ** (-i / 128)) for i in range(128)]
+    temb = t2([sil(a) for a in t1(feats)])
+    e = cond(list(z))
+    s = [sil(a + b) for a, b in zip(temb, e)]
+    h = inp(list(x))
+    for _ in range(L):
+        mod, fc1, fc2 = lin(3 * W, W), lin(W, W), lin(W, W)
+        m = mod(s)
+        u = [a * (1 + m[W + i]) + m[i] for i, a in enumerate(ln(h))]
+        u = fc2([sil(a) for a in fc1(u)])
+        h = [h[i] + m[2 * W + i] * u[i] for i in range(W)]
+    fmod, outl = lin(2 * W, W), lin(2 * D, W)
+    m = fmod(s)
+    o = outl([a * (1 + m[W + i]) + m[i] for i, a in enumerate(ln(h))])
+    assert pos[0] == len(blob)
+    skip = cfg.eps_skip_gain * math.sqrt(1 - sched.abar[t])
+    return [o[d] + skip * x[d] for d in range(D)], o[D:]
+
+
+@pytest.mark.parametrize("gain", [0.0, 1.0])
+def test_head_forward_matches_scalar_loops(gain):
+    shape = S.HeadShape(4, 3, 8, 2)
+    blob = S.head_weights(shape, 11, out_scale=0.7, bias_std=0.3)
+    cfg = O.HeadCfg(4, 3, 8, 2, 5, eps_skip_gain=gain)
+    head = O.Head(cfg, blob)
+    rng = np.random.default_rng(3)
+    x, z = rng.normal(size=(3, 4)), rng.normal(size=(3, 3))
+    for t in (1, 3, 5):
+        eh, v = head.forward(x, t, head.cond_embed(z))
+        for r in range(3):
+            eh_s, v_s = _scalar_head_forward(cfg, blob, head.sched, x[r], t, z[r])
+            assert np.allclose(eh[r], eh_s, rtol=1e-11, atol=1e-12)
+            assert np.allclose(v[r], v_s, rtol=1e-11, atol=1e-12)
+
+
+def test_oracle_and_generator_agree_on_blob_layout():
+    shape = S.HeadShape(16, 64, 128, 2)
+    cfg = O.HeadCfg(16, 64, 128, 2, 10)
+    assert [(n, tuple(s)) for n, s in O.head_param_shapes(cfg)] == \
+           [(n, tuple(s)) for n, s in S.param_layout(shape)]
+
+
+def _set(blob, shape, name, value):
+    off = 0
+    for n, s in S.param_layout(shape):
+        k = int(np.prod(s))
+        if n == name:
+            blob[off:off + k] = value
+        off += k
+
+
+def test_head_structure_invariants():
+    shape = S.HeadShape(8, 5, 32, 3)
+    cfg = O.HeadCfg(8, 5, 32, 3, 6)
+    rng = np.random.default_rng(4)
+    x, z = rng.normal(size=(4, 8)), rng.normal(size=(4, 5))
+    blob = S.head_weights(shape, 5, bias_std=0.2)
+    # layer norm: zero mean, unit (biased) variance
+    ln = O.layernorm(rng.normal(size=(4, 32)) * 3 + 1, 0.0)
+    assert np.allclose(ln.mean(-1), 0, atol=1e-12) and np.allclose((ln ** 2).mean(-1), 1)
+    # gates zero -> every block is the identity: output is the modulated LN of W_in x + b_in
+    b2 = blob.copy()
+    for l in range(3):
+        off = 0
+        for n, s in S.param_layout(shape):
+            k = int(np.prod(s))
+            if n == f"blk{l}.mod.w":
+                b2[off + 2 * 32 * 32: off + k] = 0       # rows [2W,3W) produce the gate
+            if n == f"blk{l}.mod.b":
+                b2[off + 2 * 32: off + k] = 0
+            off += k
+    hd = O.Head(cfg, b2)
+    e = hd.cond_embed(z)
+    eh, v = hd.forward(x, 2, e)
+    s = O.silu(hd.time_emb[2] + e)
+    m = s @ hd.p["fmod.w"].T + hd.p["fmod.b"]
+    h = x @ hd.p["in.w"].T + hd.p["in.b"]
+    o = (O.layernorm(h, 1e-6) * (1 + m[:, 32:]) + m[:, :32]) @ hd.p["out.w"].T + hd.p["out.b"]
+    assert np.allclose(np.concatenate([eh, v], 1), o, rtol=1e-12)
+    # the time step matters, and so does the conditioning
+    hd = O.Head(cfg, blob)
+    e = hd.cond_embed(z)
+    a, _ = hd.forward(x, 2, e)
+    b, _ = hd.forward(x, 3, e)
+    c, _ = hd.forward(x, 2, hd.cond_embed(z + 1))
+    assert not np.allclose(a, b) and not np.allclose(a, c)
+
+
+# -------------------------------------------------- lockstep trajectory ----
+def _tiny_pair(seed=7, out_scale=0.3, T=6, gain=1.0, same=False, bias_std=0.1):
+    shape = S.HeadShape(8, 6, 16, 2)
+    tb = S.head_weights(shape, seed, out_scale, bias_std)
+    db = tb.copy() if same else S.perturbed_copy(tb, shape, seed + 1, 0.2, out_scale)
+    cfg = O.HeadCfg(8, 6, 16, 2, T, eps_skip_gain=gain)
+    return shape, cfg, O.Head(cfg, tb), O.Head(cfg, db)
+
+
+def test_alignment_cancels_the_exponentials():
+    """Under shared eps_t the per-step ratio is sqrt|Sigma^q|/sqrt|Sigma^p|
+    (Eq. 6): the sum of full log-density differences equals log Sigma."""
+    _, _, tgt, drf = _tiny_pair()
+    zq, zp = S.cond_vectors(32, 6, 3, add_std=0.3)
+    for tau in (1.0, 0.8):
+        summ, ex = O.denoise_lockstep(drf, tgt, zq, zp, seed=9, tau=tau)
+        assert np.allclose(ex["log_sigma_full"], summ[:, -1], rtol=1e-9, atol=1e-9)
+        assert np.std(summ[:, -1]) > 1e-3        # not vacuous: variances differ
+    # without alignment the exponentials do not cancel
+    summ, ex = O.denoise_lockstep(drf, tgt, zq, zp, seed=9, aligned=False)
+    assert not np.allclose(ex["log_sigma_full"], summ[:, -1], atol=1e-3)
+
+
+def test_identical_heads_accept_everything():
+    """Identical draft and target (weights and cond) give ratio exactly 1."""
+    _, _, tgt, drf = _tiny_pair(same=True)
+    zq, _ = S.cond_vectors(24, 6, 5, add_std=0.0)
+    for seed in (1, 2, 3):
+        summ, _ = O.denoise_lockstep(drf, tgt, zq, zq, seed=seed)
+        n_acc, ell, mask, _ = O.verify(summ, 6, 4, seed)
+        assert np.all(ell == 0.0) and np.all(mask == 1) and np.all(n_acc == 4)
+        tok, n_out, trips, flags, _ = O.resample(summ, n_acc, 6, 4, seed)
+        assert np.all(n_out == 4) and np.all(trips == 0) and np.all(flags == 0)
+        assert np.array_equal(tok[:, :4].reshape(24, 8), summ[:, 32:40])
+
+
+@pytest.mark.parametrize("gain", [0.0, 1.0])
+def test_zero_output_layer_gives_closed_form_trajectory(gain):
+    """eps_hat = gain*sqrt(1-abar_t) x_t, v = 0: x_{t-1} = a_t x_t + sigma_t eps_t with
+    a_t = (1 - gain*beta_t)/sqrt(alpha_t), sigma_t^2 = sqrt(beta_t beta~_t):
+    x_0 is a fixed linear function of the noise slots."""
+    shape, cfg, _, _ = _tiny_pair(T=8, gain=gain)
+    blob = S.head_weights(shape, 3, bias_std=0.1)
+    _set(blob, shape, "out.w", 0.0)
+    _set(blob, shape, "out.b", 0.0)
+    cfg = O.HeadCfg(8, 6, 16, 2, 8, eps_skip_gain=gain)
+    h = O.Head(cfg, blob)
+    zq, zp = S.cond_vectors(5, 6, 1, add_std=1.0)
+    seed, off, tau = 77, 1000, 0.9
+    summ, _ = O.denoise_lockstep(h, h, zq, zp, seed=seed, row_offset=off, tau=tau)
+    s = h.sched
+    rows = off + np.arange(5, dtype=np.uint64)
+    x = O.normals(seed, rows, 8, O.STREAM_TRAJ, 8)            # x_T lives in slot T
+    for t in range(8, 0, -1):
+        a = (1 - gain * s.beta[t]) / math.sqrt(s.alpha[t])
+        sig = math.exp(0.25 * (s.log_beta[t] + s.log_beta_tilde_clip[t]))
+        if t == 1:
+            assert np.allclose(summ[:, 0:8], a * x) and np.allclose(summ[:, 16:24], a * x)
+            assert np.allclose(summ[:, 8:16], 2 * math.log(sig))
+        x = a * x + tau * sig * O.normals(seed, rows, t - 1, O.STREAM_TRAJ, 8)   # eps_t in slot t-1
+    assert np.allclose(summ[:, 32:40], x, rtol=1e-12)
+    assert np.allclose(summ[:, -1], 0.0, atol=1e-12)
+
+
+def test_theorem1_alignment_gap():
+    """E||x^q - x^p||^2 without alignment minus with alignment = 2 tr sqrt(Sigma^q Sigma^p)
+    (Theorem 1), on one reverse step with constant diagonal covariances."""
+    shape = S.HeadShape(8, 6, 16, 1)
+    R = 200000
+    heads = []
+    for k, (eb, vb) in enumerate([(0.3, 0.5), (-0.2, -0.4)]):
+        blob = S.head_weights(shape, 20 + k)
+        _set(blob, shape, "out.w", 0.0)
+        _set(blob, shape, "out.b", np.concatenate([np.full(8, eb), np.linspace(-1, 1, 8) * vb]))
+        heads.append(O.Head(O.HeadCfg(8, 6, 16, 1, 1), blob))
+    z = np.zeros((R, 6))
+    _, ex_a = O.denoise_lockstep(heads[0], heads[1], z, z, seed=5, aligned=True)
+    _, ex_u = O.denoise_lockstep(heads[0], heads[1], z, z, seed=5, aligned=False)
+    s = heads[0].sched
+    sig = []
+    for vb in (0.5, -0.4):
+        f = (np.linspace(-1, 1, 8) * vb + 1) / 2
+        sig.append(np.exp(0.5 * (f * s.log_beta[1] + (1 - f) * s.log_beta_tilde_clip[1])))
+    gap = 2 * np.sum(sig[0] * sig[1])
+    dmu2 = 8 * (s.beta[1] / math.sqrt(1 - s.abar[1]) / math.sqrt(s.alpha[1]) * 0.5) ** 2
+    assert ex_a["dist2"].mean() == pytest.approx(dmu2 + np.sum((sig[0] - sig[1]) ** 2), rel=2e-2)
+    assert ex_u["dist2"].mean() - ex_a["dist2"].mean() == pytest.approx(gap, rel=2e-2)
+
+
+# ---------------------------------------------- verify + resample (1-D) ----
+def _one_dim_summary(G, mu_p, sd_p, mu_q, sd_q, seed, log_sigma=0.0):
+    """Rows whose p and q differ in coordinate 0 only (the other three
+    coordinates are identical and cancel): a 1-D accept / resample problem."""
+    D = 4
+    mp = np.zeros((G, D)); mq = np.zeros((G, D))
+    lp = np.zeros((G, D)); lq = np.zeros((G, D))
+    mp[:, 0], mq[:, 0] = mu_p, mu_q
+    lp[:, 0], lq[:, 0] = 2 * math.log(sd_p), 2 * math.log(sd_q)
+    eps = O.normals(seed, np.arange(G, dtype=np.uint64), 0, O.STREAM_TRAJ, D)
+    x0 = mq + np.exp(0.5 * lq) * eps                      # the draft sample
+    return np.concatenate([mp, lp, mq, lq, x0, np.full((G, 1), log_sigma)], axis=1)
+
+
+def test_one_dim_accept_resample_is_lossless():
+    """Sigma = 1: P(accept) = 1 - TV(p,q); resampled tokens follow
+    max(0,p-q)/Z; accepted-or-resampled tokens follow p exactly; trips are
+    geometric with success probability TV (Sec. 3.1, Sec. 3.3)."""
+    G, seed = 60000, 31
+    mu_p, sd_p, mu_q, sd_q = 0.4, 0.8, -0.3, 1.1
+    summ = _one_dim_summary(G, mu_p, sd_p, mu_q, sd_q, seed)
+    n_acc, ell, mask, _ = O.verify(summ, G, 1, seed)
+    p = lambda x: stats.norm.pdf(x, mu_p, sd_p)
+    q = lambda x: stats.norm.pdf(x, mu_q, sd_q)
+    tv, _ = integrate.quad(lambda x: max(0.0, p(x) - q(x)), -12, 12, limit=400)
+    se = math.sqrt(tv * (1 - tv) / G)
+    assert mask.mean() == pytest.approx(1 - tv, abs=4 * se)
+    tok, n_out, trips, flags, _ = O.resample(summ, n_acc, G, 1, seed)
+    assert np.all(flags == 0) and np.all(n_out == 1)
+    rej = n_acc == 0
+    xs = np.linspace(-12, 12, 24001)
+    res_pdf = np.maximum(0, p(xs) - q(xs))
+    res_cdf = np.cumsum(res_pdf) * (xs[1] - xs[0]) / tv
+    cdf = lambda x: np.interp(x, xs, res_cdf)
+    assert stats.kstest(tok[rej, 0, 0], cdf).pvalue > 1e-3
+    assert stats.kstest(tok[:, 0, 0], "norm", args=(mu_p, sd_p)).pvalue > 1e-3
+    # untouched coordinates of resampled tokens are plain draws from p = N(0,1)
+    assert stats.kstest(tok[rej, 0, 2], "norm").pvalue > 1e-3
+    assert trips[rej].mean() == pytest.approx(1 / tv, rel=0.03)
+    assert np.all(trips[~rej] == 0)
+    # equal-variance closed form: P(accept) = 2 Phi(-|dmu| / (2 sd))
+    summ = _one_dim_summary(G, 0.5, 0.7, -0.2, 0.7, seed + 1)
+    _, _, mask, _ = O.verify(summ, G, 1, seed + 1)
+    want = 2 * stats.norm.cdf(-0.7 / (2 * 0.7))
+    assert mask.mean() == pytest.approx(want, abs=4 * math.sqrt(want * (1 - want) / G))
+
+
+def test_sigma_factor_scales_the_ratio():
+    """log Sigma enters the ratio additively in the log domain (Eq. 7) and the
+    resampling threshold through Sigma*p (Cor. 1)."""
+    G, seed = 40000, 5
+    ls = 0.4
+    summ = _one_dim_summary(G, 0.0, 1.0, 0.0, 1.0, seed, log_sigma=-ls)
+    _, ell, mask, _ = O.verify(summ, G, 1, seed)
+    assert np.allclose(ell, -ls)
+    want = math.exp(-ls)                 # p = q: accept iff u <= Sigma
+    assert mask.mean() == pytest.approx(want, abs=4 * math.sqrt(want * (1 - want) / G))
+    # Sigma*p - q < 0 everywhere here, so resampling never accepts: cap flag
+    n_acc = np.zeros(G, dtype=np.int32)
+    tok, n_out, trips, flags, _ = O.resample(summ[:50], n_acc[:50], 50, 1, seed, max_trips=7)
+    assert np.all(flags == O.FLAG_CAP) and np.all(trips == 7) and np.all(n_out == 1)
+
+
+def test_first_reject_scan_and_emit():
+    D, gamma, G = 4, 5, 4
+    summ = np.zeros((G * gamma, 5 * D + 1))
+    summ[:, 4 * D:5 * D] = np.arange(G * gamma)[:, None] + 1.0      # x0 tags the row
+    # force per-row decisions through log Sigma: +50 accept, -50 reject
+    pattern = np.array([[1, 1, 1, 1, 1], [0, 1, 1, 1, 1], [1, 1, 0, 1, 0], [1, 1, 1, 1, 0]])
+    summ[:, -1] = np.where(pattern.reshape(-1) == 1, 50.0, -50.0)
+    n_acc, _, mask, _ = O.verify(summ, G, gamma, seed=3)
+    assert list(n_acc) == [5, 0, 2, 4] and np.array_equal(mask.reshape(G, gamma), pattern)
+    summ[:, -1] = np.where(pattern.reshape(-1) == 1, 50.0, 0.3)
+    tok, n_out, trips, flags, _ = O.resample(summ, n_acc, G, gamma, seed=3)
+    assert list(n_out) == [5, 1, 3, 5]
+    assert np.array_equal(tok[0, :5, 0], [1, 2, 3, 4, 5]) and np.all(tok[0, 5] == 0)
+    assert np.array_equal(tok[2, :2, 0], [11, 12]) and np.all(tok[2, 3:] == 0)
+    assert np.all(tok[1, 1:] == 0) and trips[0] == 0 and np.all(trips[1:] >= 1)
+
+
+def test_corollary1_two_forms_of_the_threshold():
+    """max(0, Sigma p - q)/(Sigma p) from densities equals the oracle's
+    max(0, 1 - exp(a)) (Eq. 10 vs Cor. 1)."""
+    rng = np.random.default_rng(8)
+    D = 4
+    mp, mq = rng.normal(size=(200, D)), rng.normal(size=(200, D))
+    lp, lq = rng.normal(size=(200, D)) * 0.3, rng.normal(size=(200, D)) * 0.3
+    ls = rng.normal(size=200) * 0.5
+    x = mp + np.exp(0.5 * lp) * rng.normal(size=(200, D))
+    a_s, _ = O.resample_threshold(x, mp, lp, mq, lq, ls)
+    pd = np.prod(stats.norm.pdf(x, mp, np.exp(0.5 * lp)), axis=-1)
+    qd = np.prod(stats.norm.pdf(x, mq, np.exp(0.5 * lq)), axis=-1)
+    want = np.maximum(0, np.exp(ls) * pd - qd) / (np.exp(ls) * pd)
+    assert np.allclose(a_s, want, rtol=1e-10, atol=1e-12)
+    assert (a_s == 0).any() and (a_s > 0).any()
+
+
+def test_verify_uses_the_draft_sample_and_both_densities():
+    """ratio = Sigma p(x0|x1^p)/q(x0|x1^q) with x0 the DRAFT sample (Eq. 7),
+    checked against scipy densities."""
+    _, _, tgt, drf = _tiny_pair(out_scale=0.05)
+    zq, zp = S.cond_vectors(40, 6, 3, add_std=0.1)
+    tau = 0.9
+    summ, _ = O.denoise_lockstep(drf, tgt, zq, zp, seed=4, tau=tau)
+    mu_p, lv_p, mu_q, lv_q, x0, ls = O.split_summary(summ, 8)
+    eps1 = O.normals(4, np.arange(40, dtype=np.uint64), 0, O.STREAM_TRAJ, 8)
+    assert np.allclose(x0, mu_q + tau * np.exp(0.5 * lv_q) * eps1)
+    want = (ls + stats.norm.logpdf(x0, mu_p, tau * np.exp(0.5 * lv_p)).sum(-1)
+            - stats.norm.logpdf(x0, mu_q, tau * np.exp(0.5 * lv_q)).sum(-1))
+    _, ell, mask, log_u = O.verify(summ, 10, 4, seed=4, tau=tau)
+    assert np.allclose(ell, want, rtol=1e-9, atol=1e-9)
+    u = O.uniforms(4, np.arange(40, dtype=np.uint64), 0, O.STREAM_ACCEPT_U)
+    assert np.array_equal(mask, (np.log(u) <= want).astype(np.uint8))
+    assert 0 < mask.mean() < 1
+
+
+def test_tiny_workload_runs_and_is_deterministic():
+    wl = S.WORKLOADS["tiny"]
+    tb, db, ds = wl.heads()
+    mk = lambda sh: O.HeadCfg(sh.token_dim, sh.cond_dim, sh.width, sh.n_blocks, wl.n_steps,
+                              eps_skip_gain=wl.eps_skip_gain)
+    tgt, drf = O.Head(mk(wl.target), tb), O.Head(mk(ds), db)
+    zq, zp = wl.conds(128)
+    a, _ = O.denoise_lockstep(drf, tgt, zq, zp, wl.seed)
+    b, _ = O.denoise_lockstep(drf, tgt, zq[64:], zp[64:], wl.seed, row_offset=64)
+    assert np.array_equal(a[64:], b)           # rows are independent and keyed globally
+    _, _, mask, _ = O.verify(a, 64, 2, wl.seed)
+    assert 0.2 < mask.mean() < 0.8
