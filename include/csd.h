@@ -1,0 +1,205 @@
+/*
+ * csd.h - C ABI of the MI355X (gfx950) hot path of continuous speculative
+ * decoding for autoregressive image generation (arxiv 2411.11925).
+ *
+ * The boundary follows the paper's statement of one speculative step (Alg. 1):
+ * the conditioning vectors that the draft model M_q and the target model M_p
+ * produce for gamma draft positions go in; the accepted-prefix length n and the
+ * tokens [x_1..x_n, x'] come out.  Everything in between runs in HIP kernels of
+ * this library: the T-step reverse diffusion of both heads on one aligned
+ * trajectory (shared reparameterisation noise eps_t, Sec. 3.2 and App. A.2),
+ * log Sigma of Eq. 6, the accept test of Eq. 7 / Alg. 1, and acceptance-rejection
+ * resampling from max(0,p-q)/Z with the threshold of Corollary 1 (Sec. 3.3).
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the head's device, owned by the
+ *     caller; "host" pointers are ordinary host memory.  The library owns only
+ *     what csd_init_head allocates (freed by csd_free_head).
+ *   - All matrices are row-major.  A row is one (image, draft position) pair;
+ *     group g holds rows g*gamma .. g*gamma+gamma-1; R = n_groups*gamma.
+ *   - `hip_stream` is a hipStream_t (NULL = the default stream).  Calls enqueue
+ *     work and return; outputs are valid once the stream has been synchronised.
+ *     No call synchronises the device except csd_init_head / csd_free_head.
+ *   - Every function returning int gives 0 (CSD_OK) or a negative CSD_E* code;
+ *     csd_last_error() then holds a message (thread-local).  Nothing aborts.
+ *   - Random numbers come from Philox-4x32-10 keyed by `seed` and countered by
+ *     the GLOBAL row index row_offset + r, so a workload may be split over
+ *     calls (or devices) without changing any result.
+ */
+#ifndef CSD_H
+#define CSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CSD_OK            0
+#define CSD_EINVAL       (-1)  /* bad argument: null pointer, shape or size out of range */
+#define CSD_ENOMEM       (-2)  /* host or device allocation failed */
+#define CSD_EHIP         (-3)  /* a HIP runtime call failed */
+#define CSD_EUNSUPPORTED (-4)  /* valid request that this build does not implement */
+
+#define CSD_F32   0            /* GEMMs in fp32 (vector FMA) */
+#define CSD_BF16  1            /* GEMMs on bf16 MFMA with fp32 accumulation */
+
+#define CSD_COSINE 0           /* native T-step cosine schedule, betas clipped at 0.999 */
+#define CSD_TABLE  1           /* caller supplies alpha_bar[0..T] */
+
+#define CSD_TIME_FEATURES 256  /* sinusoidal features of the step index */
+
+/* streams of the counter-based generator (third counter word = slot | stream << 16) */
+#define CSD_STREAM_TRAJ        0  /* slot T: x_T; slot t-1: eps_t of the step t -> t-1 */
+#define CSD_STREAM_ACCEPT_U    1  /* slot 0: the uniform r_i of the accept test */
+#define CSD_STREAM_RESAMPLE_N  2  /* slot k: proposal noise of resampling trial k */
+#define CSD_STREAM_RESAMPLE_U  3  /* slot k: uniform of resampling trial k */
+
+/* bits of flags[g] written by csd_resample */
+#define CSD_FLAG_CAP        1u    /* max_trips reached; the last proposal was emitted */
+#define CSD_FLAG_NONFINITE  2u    /* a NaN log-ratio was met and treated as "do not accept" */
+
+typedef struct csd_head csd_head_t;   /* opaque; immutable after csd_init_head */
+
+/*
+ * One diffusion head: (eps_hat, v) = Head(x_t, t, z).  The paper leaves the
+ * network open ("a neural network with parameter theta", Sec. 3.1); this
+ * library implements an adaLN-modulated residual MLP:
+ *   E_t  = Lin_t2(SiLU(Lin_t1(sincos_256(t_scale*(t-1)))))      (per step, at init)
+ *   e    = Lin_cond(z);  s = SiLU(E_t + e);  h = Lin_in(x_t)
+ *   L x : (shift,scale,gate) = Lin_mod_l(s);  u = LN(h)*(1+scale)+shift;
+ *         h += gate * Lin_fc2_l(SiLU(Lin_fc1_l(u)))
+ *   (shift,scale) = Lin_fmod(s);  o = Lin_out(LN(h)*(1+scale)+shift)   in R^{2D}
+ *   eps_hat = o[0:D] + eps_skip_gain*sqrt(1-abar_t)*x_t ;  v = o[D:2D]
+ * LN has no affine part and uses the biased variance.  The reverse transition
+ * (Eq. 3) is N(mu_t, diag sigma_t^2) with
+ *   mu_t = (x_t - beta_t/sqrt(1-abar_t)*eps_hat)/sqrt(alpha_t),
+ *   log sigma_t^2 = f*log(beta_t) + (1-f)*log(beta~_t), f=(v+1)/2, beta~_1 := beta~_2.
+ *
+ * Packed weight order (fp32, each matrix [out,in] row-major, bias after matrix):
+ *   t1[W,256] t2[W,W] cond[W,C] in[W,D] { mod_l[3W,W] fc1_l[W,W] fc2_l[W,W] }xL
+ *   fmod[2W,W] out[2D,W]
+ * Limits: token_dim in {4,8,16}; width a multiple of 64, <= 4096; cond_dim a
+ * multiple of 8; 1 <= n_blocks <= 64; 1 <= n_steps <= 4096.
+ */
+typedef struct {
+    int32_t token_dim;       /* D */
+    int32_t cond_dim;        /* C */
+    int32_t width;           /* W */
+    int32_t n_blocks;        /* L */
+    int32_t n_steps;         /* T */
+    int32_t gemm_dtype;      /* CSD_F32 | CSD_BF16 */
+    int32_t schedule;        /* CSD_COSINE | CSD_TABLE */
+    int32_t reserved;        /* must be 0 */
+    const double* alpha_bar; /* host [n_steps+1], alpha_bar[0]=1, strictly decreasing; CSD_TABLE only */
+    float ln_eps;            /* <= 0 selects 1e-6 */
+    float t_scale;           /* <= 0 selects 1000/T */
+    float eps_skip_gain;     /* 0 = plain eps-prediction */
+    float reserved2;         /* must be 0 */
+} csd_head_cfg_t;
+
+/* Number of fp32 values in the packed weight blob of `cfg`, 0 if cfg is invalid. */
+size_t csd_param_count(const csd_head_cfg_t* cfg);
+
+/*
+ * Copies and packs `weights_host` (host, csd_param_count(cfg) floats; the
+ * caller keeps its blob) onto HIP device `device`, computes the schedule
+ * constants and the time-embedding table there, and returns the head in *out.
+ * Synchronises `device`.  Errors: CSD_EINVAL (limits above, n_floats mismatch,
+ * bad alpha_bar), CSD_ENOMEM, CSD_EHIP.
+ */
+int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n_floats,
+                  int device, csd_head_t** out);
+
+/* Frees the head's device and host memory (NULL is allowed).  Synchronises its device. */
+void csd_free_head(csd_head_t* head);
+
+/*
+ * Bytes of device workspace csd_denoise_lockstep / csd_head_eval need for
+ * n_rows rows with these heads (either head may be NULL).  0 on invalid input.
+ */
+size_t csd_workspace_bytes(const csd_head_t* draft, const csd_head_t* target, int64_t n_rows);
+
+/*
+ * Lockstep denoising on the aligned trajectory (Sec. 3.2; App. A.2; Alg. 1,
+ * "keep the eps_t the same").  For each row r: x_T^q = x_T^p = eps_T, then for
+ * t = T..1 both heads take x_{t-1} = mu_t + temperature*sigma_t*eps_t with the
+ * same eps_t, and for t = T..2 the row accumulates
+ *   log Sigma += 1/2 sum_d (log sigma^2_{q,t,d} - log sigma^2_{p,t,d})   (Eq. 6).
+ * Output summary [R, 5D+1] fp32 (device):
+ *   [ mu^p_1 | log sigma^2_{p,1} | mu^q_1 | log sigma^2_{q,1} | x_0 | log Sigma ]
+ * where x_0 = mu^q_1 + temperature*sigma_{q,1}*eps_1 is the draft token (Eq. 7).
+ * z_q, z_p: device [R, C] fp32 conditioning vectors of M_q and M_p.
+ * Both heads must share token_dim, n_steps and device; `workspace` is device
+ * memory of at least csd_workspace_bytes(draft,target,R) bytes, 256-byte
+ * aligned, free for other use once the stream has passed this call.
+ * n_groups = 0 is a no-op.  Errors: CSD_EINVAL, CSD_EHIP.
+ */
+int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target,
+                         const float* z_q, const float* z_p,
+                         int64_t n_groups, int32_t gamma,
+                         uint64_t seed, uint64_t row_offset, float temperature,
+                         float* summary, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/*
+ * Accept test and first-reject scan (Alg. 1; Eq. 7).  Per row
+ *   log_ratio = log Sigma + log N(x_0; mu^p_1, (temperature*sigma_{p,1})^2)
+ *                         - log N(x_0; mu^q_1, (temperature*sigma_{q,1})^2),
+ * r ~ U(0,1) from stream CSD_STREAM_ACCEPT_U; the row is accepted iff
+ * log r <= log_ratio (a NaN ratio rejects).  n_accept[g] = number of leading
+ * accepted rows of group g (gamma if none is rejected).
+ * summary: device [R,5D+1]; n_accept: device int32 [G]; log_ratio (device fp32
+ * [R]) and mask (device uint8 [R], 1 = accepted) may be NULL.  gamma <= 64.
+ */
+int csd_verify(const float* summary, int64_t n_groups, int32_t gamma, int32_t token_dim,
+               uint64_t seed, uint64_t row_offset, float temperature,
+               int32_t* n_accept, float* log_ratio, uint8_t* mask, void* hip_stream);
+
+/*
+ * Acceptance-rejection resampling from max(0,p-q)/Z and emit (Sec. 3.3, Cor. 1;
+ * Alg. 1 repeat-until and return).  For each group with n = n_accept[g] < gamma,
+ * at its first rejected row j: for k = 0,1,.. propose
+ *   x' = mu^p_1 + temperature*sigma_{p,1}*eps'_k,
+ *   a = log q(x'|x_1^q) - log Sigma - log p(x'|x_1^p),  alpha_s = max(0, 1-exp(a)),
+ * and stop at the first k with u_k <= alpha_s (u_k from CSD_STREAM_RESAMPLE_U).
+ * tokens: device fp32 [G, gamma+1, D] = [x_1..x_n, x', 0..]; n_out[g] = n+1, or
+ * gamma when the whole group was accepted; trips[g] = trials used (0 if none);
+ * flags[g]: CSD_FLAG_* bits.  1 <= max_trips <= 65535.  trips/flags may be NULL.
+ */
+int csd_resample(const float* summary, const int32_t* n_accept,
+                 int64_t n_groups, int32_t gamma, int32_t token_dim,
+                 uint64_t seed, uint64_t row_offset, float temperature, int32_t max_trips,
+                 float* tokens, int32_t* n_out, int32_t* trips, uint32_t* flags,
+                 void* hip_stream);
+
+/*
+ * Stage-wise access for tests and profiling: one head evaluation
+ * (eps_hat, v) = Head(x_t, t, z) for n_rows rows (definition above).
+ * x: device [n_rows, D] fp32; z: device [n_rows, C] fp32; t in 1..T;
+ * out: device [n_rows, 2D] fp32 = [eps_hat | v].  Workspace as for
+ * csd_denoise_lockstep with this head alone.
+ */
+int csd_head_eval(const csd_head_t* head, const float* x, const float* z, int32_t t,
+                  int64_t n_rows, float* out, void* workspace, size_t workspace_bytes,
+                  void* hip_stream);
+
+/*
+ * Stage-wise access to the generator: out[r, 0:n_cols] (device fp32) for global
+ * rows row_offset + r, r < n_rows.  csd_rng_normals: n_cols standard normals
+ * (a multiple of 4), element 4b+j from counter block b.  csd_rng_uniforms:
+ * n_cols = 1, the 23-bit uniform of block 0.  slot < 65536, stream_id < 65536.
+ */
+int csd_rng_normals(uint64_t seed, uint64_t row_offset, int64_t n_rows, int32_t slot,
+                    int32_t stream_id, int32_t n_cols, float* out, void* hip_stream);
+int csd_rng_uniforms(uint64_t seed, uint64_t row_offset, int64_t n_rows, int32_t slot,
+                     int32_t stream_id, float* out, void* hip_stream);
+
+/* Message of the last failing call on this thread ("" if none). */
+const char* csd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSD_H */

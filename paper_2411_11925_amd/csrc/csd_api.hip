@@ -1,0 +1,424 @@
+// C ABI of libcsd: argument checking, head set-up, and the host-side sequencing of
+// the kernels of one lockstep denoising call.  See include/csd.h for the contract.
+#include <cmath>
+#include <cstdio>
+#include <cstdarg>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "internal.hpp"
+
+using namespace csd;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap; va_start(ap, fmt); vsnprintf(buf, sizeof buf, fmt, ap); va_end(ap);
+    g_err = buf;
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                         \
+    do { hipError_t e_ = (expr);                                                              \
+         if (e_ != hipSuccess) return fail(CSD_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+bool cfg_ok(const csd_head_cfg_t* c, const char** why) {
+    if (!c) { *why = "cfg is NULL"; return false; }
+    if (!(c->token_dim == 4 || c->token_dim == 8 || c->token_dim == 16)) { *why = "token_dim must be 4, 8 or 16"; return false; }
+    if (c->width < 64 || c->width > 4096 || c->width % 64) { *why = "width must be a multiple of 64 in [64,4096]"; return false; }
+    if (c->cond_dim < 8 || c->cond_dim > 16384 || c->cond_dim % 8) { *why = "cond_dim must be a multiple of 8 in [8,16384]"; return false; }
+    if (c->n_blocks < 1 || c->n_blocks > 64) { *why = "n_blocks must be in [1,64]"; return false; }
+    if (c->n_steps < 1 || c->n_steps > 4096) { *why = "n_steps must be in [1,4096]"; return false; }
+    if (c->gemm_dtype != CSD_F32 && c->gemm_dtype != CSD_BF16) { *why = "gemm_dtype must be CSD_F32 or CSD_BF16"; return false; }
+    if (c->schedule != CSD_COSINE && c->schedule != CSD_TABLE) { *why = "schedule must be CSD_COSINE or CSD_TABLE"; return false; }
+    if (c->schedule == CSD_TABLE && !c->alpha_bar) { *why = "CSD_TABLE needs alpha_bar"; return false; }
+    if (c->reserved != 0 || c->reserved2 != 0.f) { *why = "reserved fields must be 0"; return false; }
+    if (!(c->eps_skip_gain == c->eps_skip_gain)) { *why = "eps_skip_gain is NaN"; return false; }
+    return true;
+}
+
+size_t param_count(const csd_head_cfg_t* c) {
+    const size_t D = c->token_dim, C = c->cond_dim, W = c->width, L = c->n_blocks;
+    size_t n = W * CSD_TIME_FEATURES + W + W * W + W + W * C + W + W * D + W;
+    n += L * (3 * W * W + 3 * W + 2 * (W * W + W));
+    n += 2 * W * W + 2 * W + 2 * D * W + 2 * D;
+    return n;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// device buffers of one head for R rows, carved from the caller's workspace
+struct HeadWs {
+    float* e; void* s; void* mod; void* fm; float* h; void* u; void* a; float* x; float* acc;
+};
+
+size_t head_ws_bytes(const csd_head* hd, int64_t R) {
+    const size_t r = (size_t)R, W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
+    size_t n = 0;
+    n += align_up(r * W * 4, 256);          // e
+    n += align_up(r * W * act, 256);        // s
+    n += align_up(r * 3 * W * act, 256);    // mod (one block at a time)
+    n += align_up(r * 2 * W * act, 256);    // fm
+    n += align_up(r * W * 4, 256);          // h
+    n += align_up(r * W * act, 256);        // u
+    n += align_up(r * W * act, 256);        // a
+    n += align_up(r * hd->D * 4, 256);      // x
+    n += align_up(r * 4, 256);              // acc
+    return n;
+}
+
+char* carve(const csd_head* hd, int64_t R, char* p, HeadWs* ws) {
+    const size_t r = (size_t)R, W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
+    auto take = [&](size_t bytes) { char* q = p; p += align_up(bytes, 256); return q; };
+    ws->e = (float*)take(r * W * 4);
+    ws->s = take(r * W * act);
+    ws->mod = take(r * 3 * W * act);
+    ws->fm = take(r * 2 * W * act);
+    ws->h = (float*)take(r * W * 4);
+    ws->u = take(r * W * act);
+    ws->a = take(r * W * act);
+    ws->x = (float*)take(r * hd->D * 4);
+    ws->acc = (float*)take(r * 4);
+    return p;
+}
+
+hipError_t gemm(const csd_head* hd, GemmArgs g, hipStream_t st) {
+    return hd->cfg.gemm_dtype == CSD_BF16 ? launch_gemm_bf16(g, st) : launch_gemm_f32(g, st);
+}
+
+// e = W_c z + b_c (once per call; fp32 in both modes)
+hipError_t cond_embed(const csd_head* hd, const float* z, const HeadWs& ws, int64_t R, hipStream_t st) {
+    GemmArgs g{};
+    g.A = z; g.lda = hd->C; g.B = hd->cond.w; g.bias = hd->cond.b; g.C = ws.e; g.ldc = hd->W;
+    g.M = (int)R; g.N = hd->W; g.K = hd->C; g.epi = EPI_BIAS; g.c_is_f32 = 1;
+    return launch_gemm_f32(g, st);
+}
+
+// everything of step t up to (not including) the final kernel: leaves h and fm ready
+hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hipStream_t st) {
+    const int W = hd->W;
+    const bool b16 = hd->cfg.gemm_dtype == CSD_BF16;
+    const int act = b16 ? ACT_BF16 : ACT_F32;
+    const size_t asz = b16 ? 2 : 4;
+    hipError_t e;
+    if ((e = launch_cond_silu(ws.e, hd->d_time_emb + (size_t)t * W, ws.s, act, R, W, st)) != hipSuccess) return e;
+    if ((e = launch_inproj(ws.x, hd->in.w, hd->in.b, ws.h, R, hd->D, W, st)) != hipSuccess) return e;
+    for (int l = 0; l < hd->L; ++l) {
+        GemmArgs g{};
+        g.M = (int)R; g.K = W;
+        // (shift, scale, gate) = Lin_mod(s)
+        g.A = ws.s; g.lda = W; g.B = b16 ? (const void*)hd->mod[l].w16 : (const void*)hd->mod[l].w;
+        g.bias = hd->mod[l].b; g.C = ws.mod; g.ldc = 3 * W; g.N = 3 * W; g.epi = EPI_BIAS;
+        if ((e = gemm(hd, g, st)) != hipSuccess) return e;
+        if ((e = launch_ln_mod(ws.h, ws.mod, 3 * W, ws.u, act, hd->ln_eps, R, W, st)) != hipSuccess) return e;
+        // a = silu(fc1 u)
+        g.A = ws.u; g.B = b16 ? (const void*)hd->fc1[l].w16 : (const void*)hd->fc1[l].w;
+        g.bias = hd->fc1[l].b; g.C = ws.a; g.ldc = W; g.N = W; g.epi = EPI_BIAS_SILU;
+        if ((e = gemm(hd, g, st)) != hipSuccess) return e;
+        // h += gate * fc2 a
+        g.A = ws.a; g.B = b16 ? (const void*)hd->fc2[l].w16 : (const void*)hd->fc2[l].w;
+        g.bias = hd->fc2[l].b; g.C = ws.h; g.ldc = W; g.N = W; g.epi = EPI_GATE_RES;
+        g.gate = (const char*)ws.mod + (size_t)2 * W * asz; g.ldg = 3 * W;
+        if ((e = gemm(hd, g, st)) != hipSuccess) return e;
+    }
+    GemmArgs g{};
+    g.M = (int)R; g.K = W; g.A = ws.s; g.lda = W;
+    g.B = b16 ? (const void*)hd->fmod.w16 : (const void*)hd->fmod.w; g.bias = hd->fmod.b;
+    g.C = ws.fm; g.ldc = 2 * W; g.N = 2 * W; g.epi = EPI_BIAS;
+    return gemm(hd, g, st);
+}
+
+FinalArgs final_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
+    FinalArgs f{};
+    f.h = ws.h; f.fmod = ws.fm; f.ldm = 2 * hd->W;
+    f.act = hd->cfg.gemm_dtype == CSD_BF16 ? ACT_BF16 : ACT_F32;
+    f.w_out = hd->out.w; f.b_out = hd->out.b; f.ln_eps = hd->ln_eps;
+    f.R = R; f.W = hd->W; f.D = hd->D; f.x = ws.x; f.acc = ws.acc;
+    f.coef = hd->coef[t]; f.t = t;
+    return f;
+}
+
+struct DeviceGuard {
+    int prev = -1; bool ok = false;
+    explicit DeviceGuard(int dev) { if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess) ok = true; }
+    ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* csd_last_error(void) { return g_err.c_str(); }
+
+size_t csd_param_count(const csd_head_cfg_t* cfg) {
+    const char* why;
+    if (!cfg_ok(cfg, &why)) { g_err = why; return 0; }
+    return param_count(cfg);
+}
+
+void csd_free_head(csd_head_t* h) {
+    if (!h) return;
+    DeviceGuard dg(h->device);
+    (void)hipDeviceSynchronize();
+    if (h->d_weights) (void)hipFree(h->d_weights);
+    if (h->d_weights16) (void)hipFree(h->d_weights16);
+    if (h->d_time_emb) (void)hipFree(h->d_time_emb);
+    delete h;
+}
+
+int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n_floats, int device,
+                  csd_head_t** out) {
+    const char* why = "";
+    if (!out) return fail(CSD_EINVAL, "csd_init_head: out is NULL");
+    *out = nullptr;
+    if (!cfg_ok(cfg, &why)) return fail(CSD_EINVAL, "csd_init_head: %s", why);
+    if (!weights_host) return fail(CSD_EINVAL, "csd_init_head: weights_host is NULL");
+    if (n_floats != param_count(cfg))
+        return fail(CSD_EINVAL, "csd_init_head: n_floats = %zu, config needs %zu", n_floats, param_count(cfg));
+    int n_dev = 0;
+    HIP_TRY(hipGetDeviceCount(&n_dev));
+    if (device < 0 || device >= n_dev) return fail(CSD_EINVAL, "csd_init_head: device %d of %d", device, n_dev);
+
+    csd_head* h = new (std::nothrow) csd_head();
+    if (!h) return fail(CSD_ENOMEM, "csd_init_head: host allocation failed");
+    h->cfg = *cfg; h->cfg.alpha_bar = nullptr; h->device = device;
+    h->D = cfg->token_dim; h->C = cfg->cond_dim; h->W = cfg->width; h->L = cfg->n_blocks; h->T = cfg->n_steps;
+    h->ln_eps = cfg->ln_eps > 0.f ? cfg->ln_eps : 1e-6f;
+    const int D = h->D, C = h->C, W = h->W, L = h->L, T = h->T;
+
+    // ---- schedule constants in double (Eq. 3 with the learned-range variance)
+    std::vector<double> abar(T + 1, 1.0);
+    if (cfg->schedule == CSD_TABLE) {
+        for (int t = 0; t <= T; ++t) abar[t] = cfg->alpha_bar[t];
+        bool ok = abar[0] == 1.0;
+        for (int t = 1; t <= T && ok; ++t) ok = abar[t] > 0.0 && abar[t] < abar[t - 1];
+        if (!ok) { delete h; return fail(CSD_EINVAL, "csd_init_head: alpha_bar must start at 1 and decrease strictly within (0,1]"); }
+    } else {
+        auto f = [&](int t) { const double c = std::cos((((double)t / T) + 0.008) / 1.008 * M_PI / 2.0); return c * c; };
+        for (int t = 1; t <= T; ++t) {
+            const double b = std::fmin(1.0 - f(t) / f(t - 1), 0.999);
+            abar[t] = abar[t - 1] * (1.0 - b);
+        }
+    }
+    h->coef.assign(T + 1, StepCoef{0, 0, 0, 0});
+    std::vector<double> lbt(T + 2, 0.0), lb(T + 2, 0.0);
+    for (int t = 1; t <= T; ++t) {
+        const double alpha = abar[t] / abar[t - 1], beta = 1.0 - alpha;
+        lb[t] = std::log(beta);
+        if (t >= 2) lbt[t] = std::log(beta * (1.0 - abar[t - 1]) / (1.0 - abar[t]));
+    }
+    lbt[1] = (T >= 2) ? lbt[2] : lb[1];       // posterior variance is 0 at t = 1: clipped to the next one
+    h->ref_log_sigma = 0.0;
+    for (int t = 1; t <= T; ++t) {
+        const double alpha = abar[t] / abar[t - 1], beta = 1.0 - alpha;
+        const double co = beta / (std::sqrt(1.0 - abar[t]) * std::sqrt(alpha));
+        const double cx = 1.0 / std::sqrt(alpha) - co * (double)cfg->eps_skip_gain * std::sqrt(1.0 - abar[t]);
+        h->coef[t] = StepCoef{(float)cx, (float)co, (float)(0.5 * (lb[t] + lbt[t])), (float)(0.5 * (lb[t] - lbt[t]))};
+        if (t >= 2) h->ref_log_sigma += 0.5 * D * 0.5 * (lb[t] + lbt[t]);
+    }
+    h->skip_sqrt.assign(T + 1, 0.f);
+    for (int t = 1; t <= T; ++t) h->skip_sqrt[t] = (float)((double)cfg->eps_skip_gain * std::sqrt(1.0 - abar[t]));
+
+    DeviceGuard dg(device);
+    if (!dg.ok) { delete h; return fail(CSD_EHIP, "csd_init_head: cannot select device %d", device); }
+    int rc = CSD_OK;
+    float* d_feats = nullptr; float* d_tmp = nullptr;
+    auto bail = [&](int code) { if (d_feats) (void)hipFree(d_feats); if (d_tmp) (void)hipFree(d_tmp); csd_free_head(h); return code; };
+#define INIT_TRY(expr)                                                                                  \
+    do { hipError_t e_ = (expr);                                                                        \
+         if (e_ != hipSuccess) {                                                                        \
+             rc = fail(e_ == hipErrorOutOfMemory ? CSD_ENOMEM : CSD_EHIP, "csd_init_head: %s: %s", #expr, \
+                       hipGetErrorString(e_));                                                          \
+             return bail(rc); } } while (0)
+
+    INIT_TRY(hipMalloc((void**)&h->d_weights, n_floats * sizeof(float)));
+    INIT_TRY(hipMemcpy(h->d_weights, weights_host, n_floats * sizeof(float), hipMemcpyHostToDevice));
+
+    // ---- carve the blob into layers (order documented in csd.h)
+    size_t off = 0, n16 = 0;
+    const bool b16 = cfg->gemm_dtype == CSD_BF16;
+    std::vector<Linear*> big;     // layers that get a bf16 copy
+    auto lin = [&](Linear& l, int n_out, int n_in, bool is_big) {
+        l.n_out = n_out; l.n_in = n_in;
+        l.w = h->d_weights + off; off += (size_t)n_out * n_in;
+        l.b = h->d_weights + off; off += (size_t)n_out;
+        if (is_big && b16) { big.push_back(&l); n16 += (size_t)n_out * n_in; }
+    };
+    h->mod.resize(L); h->fc1.resize(L); h->fc2.resize(L);
+    lin(h->t1, W, CSD_TIME_FEATURES, false);
+    lin(h->t2, W, W, false);
+    lin(h->cond, W, C, false);
+    lin(h->in, W, D, false);
+    for (int l = 0; l < L; ++l) { lin(h->mod[l], 3 * W, W, true); lin(h->fc1[l], W, W, true); lin(h->fc2[l], W, W, true); }
+    lin(h->fmod, 2 * W, W, true);
+    lin(h->out, 2 * D, W, false);
+    if (off != n_floats) return bail(fail(CSD_EINVAL, "csd_init_head: internal layout mismatch"));
+    if (b16) {
+        INIT_TRY(hipMalloc((void**)&h->d_weights16, n16 * sizeof(bf16_t)));
+        size_t o16 = 0;
+        for (Linear* l : big) {
+            const size_t n = (size_t)l->n_out * l->n_in;
+            INIT_TRY(launch_f32_to_bf16(l->w, h->d_weights16 + o16, n, nullptr));
+            l->w16 = h->d_weights16 + o16; o16 += n;
+        }
+    }
+
+    // ---- time embedding table E_t[t], t = 1..T: sinusoidal features in double on the
+    // host (a constant table), the two linear layers on the device in fp32
+    {
+        const int F = CSD_TIME_FEATURES, half = F / 2;
+        const double t_scale = cfg->t_scale > 0.f ? (double)cfg->t_scale : 1000.0 / T;
+        std::vector<float> feats((size_t)T * F);
+        for (int t = 1; t <= T; ++t)
+            for (int i = 0; i < half; ++i) {
+                const double a = t_scale * (t - 1) * std::exp(-std::log(10000.0) * i / half);
+                feats[(size_t)(t - 1) * F + i] = (float)std::cos(a);
+                feats[(size_t)(t - 1) * F + half + i] = (float)std::sin(a);
+            }
+        INIT_TRY(hipMalloc((void**)&d_feats, feats.size() * sizeof(float)));
+        INIT_TRY(hipMalloc((void**)&d_tmp, (size_t)T * W * sizeof(float)));
+        INIT_TRY(hipMalloc((void**)&h->d_time_emb, (size_t)(T + 1) * W * sizeof(float)));
+        INIT_TRY(hipMemcpy(d_feats, feats.data(), feats.size() * sizeof(float), hipMemcpyHostToDevice));
+        INIT_TRY(hipMemset(h->d_time_emb, 0, (size_t)W * sizeof(float)));
+        GemmArgs g{};
+        g.A = d_feats; g.lda = F; g.B = h->t1.w; g.bias = h->t1.b; g.C = d_tmp; g.ldc = W;
+        g.M = T; g.N = W; g.K = F; g.epi = EPI_BIAS_SILU;
+        INIT_TRY(launch_gemm_f32(g, nullptr));
+        g.A = d_tmp; g.lda = W; g.B = h->t2.w; g.bias = h->t2.b; g.C = h->d_time_emb + W; g.K = W; g.epi = EPI_BIAS;
+        INIT_TRY(launch_gemm_f32(g, nullptr));
+    }
+    INIT_TRY(hipDeviceSynchronize());
+    (void)hipFree(d_feats); (void)hipFree(d_tmp);
+#undef INIT_TRY
+    *out = h;
+    return CSD_OK;
+}
+
+size_t csd_workspace_bytes(const csd_head_t* draft, const csd_head_t* target, int64_t n_rows) {
+    if (n_rows < 0 || (!draft && !target)) return 0;
+    size_t n = 256;
+    if (draft) n += head_ws_bytes(draft, n_rows);
+    if (target) n += head_ws_bytes(target, n_rows);
+    return n;
+}
+
+int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, const float* z_q, const float* z_p,
+                         int64_t n_groups, int32_t gamma, uint64_t seed, uint64_t row_offset, float temperature,
+                         float* summary, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!draft || !target) return fail(CSD_EINVAL, "csd_denoise_lockstep: NULL head");
+    if (n_groups < 0 || gamma < 1) return fail(CSD_EINVAL, "csd_denoise_lockstep: n_groups >= 0 and gamma >= 1 required");
+    if (draft->D != target->D || draft->T != target->T || draft->device != target->device || draft->C != target->C)
+        return fail(CSD_EINVAL, "csd_denoise_lockstep: heads must share token_dim, cond_dim, n_steps and device");
+    if (!(temperature > 0.f)) return fail(CSD_EINVAL, "csd_denoise_lockstep: temperature must be > 0");
+    if (n_groups > (int64_t)(1 << 22) / gamma) return fail(CSD_EINVAL, "csd_denoise_lockstep: more than 2^22 rows in one call");
+    const int64_t R = n_groups * gamma;
+    if (R == 0) return CSD_OK;
+    if (!z_q || !z_p || !summary || !workspace) return fail(CSD_EINVAL, "csd_denoise_lockstep: NULL buffer");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(CSD_EINVAL, "csd_denoise_lockstep: workspace must be 256-byte aligned");
+    if (workspace_bytes < csd_workspace_bytes(draft, target, R))
+        return fail(CSD_EINVAL, "csd_denoise_lockstep: workspace of %zu bytes, need %zu", workspace_bytes,
+                    csd_workspace_bytes(draft, target, R));
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int D = draft->D, T = draft->T;
+    HeadWs wq, wp;
+    char* p = carve(draft, R, (char*)workspace, &wq);
+    carve(target, R, p, &wp);
+
+    HIP_TRY(launch_init_x(wq.x, wp.x, wq.acc, wp.acc, R, D, T, seed, row_offset, st));
+    HIP_TRY(cond_embed(draft, z_q, wq, R, st));
+    HIP_TRY(cond_embed(target, z_p, wp, R, st));
+    for (int t = T; t >= 1; --t) {
+        for (int which = 0; which < 2; ++which) {
+            const csd_head* hd = which ? target : draft;
+            const HeadWs& ws = which ? wp : wq;
+            HIP_TRY(head_body(hd, ws, t, R, st));
+            FinalArgs f = final_args(hd, ws, t, R);
+            f.seed = seed; f.row_offset = row_offset; f.tau = temperature;
+            f.summary = summary; f.is_target = which;
+            HIP_TRY(launch_final(f, st));
+        }
+    }
+    const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
+    HIP_TRY(launch_finish_summary(summary, wq.acc, wp.acc, ref_diff, R, D, st));
+    return CSD_OK;
+}
+
+int csd_head_eval(const csd_head_t* head, const float* x, const float* z, int32_t t, int64_t n_rows, float* out,
+                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!head) return fail(CSD_EINVAL, "csd_head_eval: NULL head");
+    if (t < 1 || t > head->T) return fail(CSD_EINVAL, "csd_head_eval: t = %d outside 1..%d", t, head->T);
+    if (n_rows < 0 || n_rows > (1 << 22)) return fail(CSD_EINVAL, "csd_head_eval: n_rows out of range");
+    if (n_rows == 0) return CSD_OK;
+    if (!x || !z || !out || !workspace) return fail(CSD_EINVAL, "csd_head_eval: NULL buffer");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(CSD_EINVAL, "csd_head_eval: workspace must be 256-byte aligned");
+    if (workspace_bytes < csd_workspace_bytes(head, nullptr, n_rows))
+        return fail(CSD_EINVAL, "csd_head_eval: workspace of %zu bytes, need %zu", workspace_bytes,
+                    csd_workspace_bytes(head, nullptr, n_rows));
+    hipStream_t st = (hipStream_t)hip_stream;
+    HeadWs ws;
+    carve(head, n_rows, (char*)workspace, &ws);
+    HIP_TRY(hipMemcpyAsync(ws.x, x, (size_t)n_rows * head->D * sizeof(float), hipMemcpyDeviceToDevice, st));
+    HIP_TRY(cond_embed(head, z, ws, n_rows, st));
+    HIP_TRY(head_body(head, ws, t, n_rows, st));
+    FinalArgs f = final_args(head, ws, t, n_rows);
+    f.raw_out = out; f.skip_coef = head->skip_sqrt[t];
+    HIP_TRY(launch_final(f, st));
+    return CSD_OK;
+}
+
+int csd_verify(const float* summary, int64_t n_groups, int32_t gamma, int32_t token_dim, uint64_t seed,
+               uint64_t row_offset, float temperature, int32_t* n_accept, float* log_ratio, uint8_t* mask,
+               void* hip_stream) {
+    if (n_groups < 0 || gamma < 1 || gamma > 64) return fail(CSD_EINVAL, "csd_verify: n_groups >= 0 and 1 <= gamma <= 64 required");
+    if (!(token_dim == 4 || token_dim == 8 || token_dim == 16)) return fail(CSD_EINVAL, "csd_verify: token_dim must be 4, 8 or 16");
+    if (!(temperature > 0.f)) return fail(CSD_EINVAL, "csd_verify: temperature must be > 0");
+    if (n_groups > (int64_t)1 << 30) return fail(CSD_EINVAL, "csd_verify: too many groups");
+    if (n_groups == 0) return CSD_OK;
+    if (!summary || !n_accept) return fail(CSD_EINVAL, "csd_verify: NULL buffer");
+    HIP_TRY(launch_verify(summary, n_groups, gamma, token_dim, seed, row_offset, temperature, n_accept, log_ratio,
+                          mask, (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
+int csd_resample(const float* summary, const int32_t* n_accept, int64_t n_groups, int32_t gamma, int32_t token_dim,
+                 uint64_t seed, uint64_t row_offset, float temperature, int32_t max_trips, float* tokens,
+                 int32_t* n_out, int32_t* trips, uint32_t* flags, void* hip_stream) {
+    if (n_groups < 0 || gamma < 1 || gamma > 64) return fail(CSD_EINVAL, "csd_resample: n_groups >= 0 and 1 <= gamma <= 64 required");
+    if (!(token_dim == 4 || token_dim == 8 || token_dim == 16)) return fail(CSD_EINVAL, "csd_resample: token_dim must be 4, 8 or 16");
+    if (!(temperature > 0.f)) return fail(CSD_EINVAL, "csd_resample: temperature must be > 0");
+    if (max_trips < 1 || max_trips > 65535) return fail(CSD_EINVAL, "csd_resample: max_trips must be in [1,65535]");
+    if (n_groups > (int64_t)1 << 30) return fail(CSD_EINVAL, "csd_resample: too many groups");
+    if (n_groups == 0) return CSD_OK;
+    if (!summary || !n_accept || !tokens || !n_out) return fail(CSD_EINVAL, "csd_resample: NULL buffer");
+    HIP_TRY(launch_resample(summary, n_accept, n_groups, gamma, token_dim, seed, row_offset, temperature, max_trips,
+                            tokens, n_out, trips, flags, (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
+int csd_rng_normals(uint64_t seed, uint64_t row_offset, int64_t n_rows, int32_t slot, int32_t stream_id,
+                    int32_t n_cols, float* out, void* hip_stream) {
+    if (n_rows < 0 || n_rows > ((int64_t)1 << 30) || slot < 0 || slot > 65535 || stream_id < 0 || stream_id > 65535 ||
+        n_cols < 4 || n_cols % 4 || n_cols > 1024)
+        return fail(CSD_EINVAL, "csd_rng_normals: argument out of range");
+    if (n_rows == 0) return CSD_OK;
+    if (!out) return fail(CSD_EINVAL, "csd_rng_normals: out is NULL");
+    HIP_TRY(launch_rng_normals(seed, row_offset, n_rows, slot, stream_id, n_cols, out, (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
+int csd_rng_uniforms(uint64_t seed, uint64_t row_offset, int64_t n_rows, int32_t slot, int32_t stream_id, float* out,
+                     void* hip_stream) {
+    if (n_rows < 0 || n_rows > ((int64_t)1 << 30) || slot < 0 || slot > 65535 || stream_id < 0 || stream_id > 65535)
+        return fail(CSD_EINVAL, "csd_rng_uniforms: argument out of range");
+    if (n_rows == 0) return CSD_OK;
+    if (!out) return fail(CSD_EINVAL, "csd_rng_uniforms: out is NULL");
+    HIP_TRY(launch_rng_uniforms(seed, row_offset, n_rows, slot, stream_id, out, (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,120 @@
+// Internal declarations shared by the translation units of libcsd (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <vector>
+
+#include "../../include/csd.h"
+
+namespace csd {
+
+typedef uint16_t bf16_t;   // storage only; conversions below
+
+__host__ __device__ inline float bf16_to_f32(bf16_t v) {
+    union { uint32_t u; float f; } c; c.u = (uint32_t)v << 16; return c.f;
+}
+// round to nearest even (NaN keeps a quiet payload bit)
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+    union { uint32_t u; float f; } c; c.f = f;
+    if ((c.u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((c.u >> 16) | 0x40u);
+    return (bf16_t)((c.u + 0x7FFFu + ((c.u >> 16) & 1u)) >> 16);
+}
+
+// per-step constants of one head's sampler, fp32 copies of host doubles
+struct StepCoef {
+    float cx;      // coefficient of x_t in mu_t, skip folded in: (1 - gain*beta_t)/sqrt(alpha_t)
+    float co;      // coefficient of -o[0:D] in mu_t: beta_t / (sqrt(1-abar_t) sqrt(alpha_t))
+    float lmid;    // (log beta_t + log beta~_t)/2: log sigma^2 at v = 0
+    float lhalf;   // (log beta_t - log beta~_t)/2: d log sigma^2 / d v
+};
+
+// one linear layer on the device: fp32 master copy and, in bf16 mode, a bf16 copy
+struct Linear {
+    const float* w = nullptr;     // [n_out, n_in]
+    const float* b = nullptr;     // [n_out]
+    const bf16_t* w16 = nullptr;  // [n_out, n_in] (bf16 mode, large layers only)
+    int n_out = 0, n_in = 0;
+};
+
+}  // namespace csd
+
+struct csd_head {
+    csd_head_cfg_t cfg;
+    int device;
+    int D, C, W, L, T;
+    float ln_eps;
+    csd::Linear t1, t2, cond, in, fmod, out;
+    std::vector<csd::Linear> mod, fc1, fc2;
+    std::vector<csd::StepCoef> coef;     // [T+1], entry 0 unused
+    std::vector<float> skip_sqrt;        // [T+1]: eps_skip_gain * sqrt(1 - abar_t)
+    double ref_log_sigma;                // sum_{t=2..T} D/2 * lmid_t in double
+    float* d_weights = nullptr;          // fp32 blob
+    csd::bf16_t* d_weights16 = nullptr;  // bf16 copies of the large matrices
+    float* d_time_emb = nullptr;         // [T+1, W]
+};
+
+namespace csd {
+
+// activation storage type by gemm dtype
+enum { ACT_F32 = 0, ACT_BF16 = 1 };
+
+// Epilogues of the GEMM C = A * B^T (+ bias)
+enum { EPI_BIAS = 0,        // C = acc + bias
+       EPI_BIAS_SILU = 1,   // C = silu(acc + bias)
+       EPI_GATE_RES = 2 };  // C(fp32) += gate * (acc + bias)
+
+struct GemmArgs {
+    const void* A; int lda;        // [M,K] activations (fp32 or bf16)
+    const void* B;                 // [N,K] weights, same type as A
+    const float* bias;             // [N] fp32
+    void* C; int ldc;              // [M,N]; fp32 for EPI_GATE_RES, else activation type
+    const void* gate; int ldg;     // [M,N] activation type (EPI_GATE_RES)
+    int M, N, K;
+    int epi;
+    int c_is_f32;                  // output type override: 1 = fp32 even in bf16 mode
+};
+
+hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st);
+hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st);
+
+// s = silu(E_t + e)
+hipError_t launch_cond_silu(const float* e, const float* time_emb_t, void* s, int act, int64_t R, int W, hipStream_t st);
+// h = W_in x + b_in
+hipError_t launch_inproj(const float* x, const float* w, const float* b, float* h, int64_t R, int D, int W, hipStream_t st);
+// u = LN(h)*(1+scale)+shift with (shift,scale) = mod[:, 0:W], mod[:, W:2W]
+hipError_t launch_ln_mod(const float* h, const void* mod, int ldm, void* u, int act, float ln_eps, int64_t R, int W, hipStream_t st);
+
+struct FinalArgs {
+    const float* h; const void* fmod; int ldm; int act;   // final LN + modulation inputs
+    const float* w_out; const float* b_out;               // [2D, W], [2D]
+    float ln_eps;
+    int64_t R; int W; int D;
+    // transition
+    float* x;                  // [R,D] in: x_t, out: x_{t-1} (not written at t = 1)
+    float* acc;                // [R] running 1/2 sum_d (log sigma^2 - lmid_t), t >= 2
+    StepCoef coef; int t;
+    uint64_t seed, row_offset; float tau;
+    float* summary; int is_target;   // t == 1: writes this head's part of the summary row
+    float* raw_out;            // optional [R,2D]: (eps_hat, v) for csd_head_eval; skips the transition
+    float skip_coef;           // eps_skip_gain * sqrt(1 - abar_t), for raw_out only
+};
+hipError_t launch_final(const FinalArgs& a, hipStream_t st);
+
+hipError_t launch_init_x(float* xq, float* xp, float* accq, float* accp, int64_t R, int D, int T,
+                         uint64_t seed, uint64_t row_offset, hipStream_t st);
+hipError_t launch_finish_summary(float* summary, const float* accq, const float* accp, float ref_diff,
+                                 int64_t R, int D, hipStream_t st);
+
+hipError_t launch_verify(const float* summary, int64_t G, int gamma, int D, uint64_t seed, uint64_t row_offset,
+                         float tau, int32_t* n_accept, float* log_ratio, uint8_t* mask, hipStream_t st);
+hipError_t launch_resample(const float* summary, const int32_t* n_accept, int64_t G, int gamma, int D,
+                           uint64_t seed, uint64_t row_offset, float tau, int max_trips,
+                           float* tokens, int32_t* n_out, int32_t* trips, uint32_t* flags, hipStream_t st);
+hipError_t launch_rng_normals(uint64_t seed, uint64_t row_offset, int64_t R, int slot, int stream_id, int n_cols,
+                              float* out, hipStream_t st);
+hipError_t launch_rng_uniforms(uint64_t seed, uint64_t row_offset, int64_t R, int slot, int stream_id,
+                               float* out, hipStream_t st);
+hipError_t launch_f32_to_bf16(const float* src, bf16_t* dst, size_t n, hipStream_t st);
+
+}  // namespace csd
