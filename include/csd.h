@@ -196,6 +196,17 @@ int csd_rng_normals(uint64_t seed, uint64_t row_offset, int64_t n_rows, int32_t 
 int csd_rng_uniforms(uint64_t seed, uint64_t row_offset, int64_t n_rows, int32_t slot,
                      int32_t stream_id, float* out, void* hip_stream);
 
+/*
+ * Stage-wise access to the bf16 MFMA GEMM of the head's dense layers:
+ *   C[M,N] = epilogue(A[M,K] * B[N,K]^T + bias[N]),  fp32 accumulation.
+ * A, B: device bf16 (raw uint16 bit patterns), dense row-major; bias: device fp32.
+ * epilogue 0: identity; 1: SiLU; 2: C(fp32) += gate * (.) with gate device bf16 [M,N].
+ * out_f32 != 0 stores C as fp32, else as bf16 (epilogue 2 always fp32).
+ * K and N must be multiples of 64; all pointers 16-byte aligned.
+ */
+int csd_gemm_bf16(const void* A, const void* B, const float* bias, int64_t M, int32_t N, int32_t K,
+                  int32_t epilogue, int32_t out_f32, void* C, const void* gate, void* hip_stream);
+
 /* Message of the last failing call on this thread ("" if none). */
 const char* csd_last_error(void);
 

@@ -30,7 +30,7 @@ CSD_FLAG_CAP, CSD_FLAG_NONFINITE = 1, 2
 
 EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_workspace_bytes",
            "csd_denoise_lockstep", "csd_verify", "csd_resample", "csd_head_eval",
-           "csd_rng_normals", "csd_rng_uniforms", "csd_last_error"]
+           "csd_rng_normals", "csd_rng_uniforms", "csd_gemm_bf16", "csd_last_error"]
 
 
 class csd_head_cfg_t(Structure):
@@ -67,6 +67,11 @@ _lib.csd_rng_normals.restype = c_int
 _lib.csd_rng_normals.argtypes = [c_uint64, c_uint64, c_int64, c_int32, c_int32, c_int32, c_void_p, c_void_p]
 _lib.csd_rng_uniforms.restype = c_int
 _lib.csd_rng_uniforms.argtypes = [c_uint64, c_uint64, c_int64, c_int32, c_int32, c_void_p, c_void_p]
+
+
+_lib.csd_gemm_bf16.restype = c_int
+_lib.csd_gemm_bf16.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32, c_int32,
+                               c_void_p, c_void_p, c_void_p]
 
 
 class CsdError(RuntimeError):
@@ -225,3 +230,21 @@ def csd_rng_uniforms(seed: int, row_offset: int, n_rows: int, slot: int, stream_
     out = torch.empty(n_rows, dtype=torch.float32, device=device)
     _check(_lib.csd_rng_uniforms(seed, row_offset, n_rows, slot, stream_id, _ptr(out), _stream(stream)))
     return out
+
+
+def csd_gemm_bf16(A: torch.Tensor, B: torch.Tensor, bias: torch.Tensor, epilogue: int = 0, out_f32: bool = False,
+                  C: torch.Tensor | None = None, gate: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """A [M,K], B [N,K], gate [M,N]: torch.bfloat16 on the device; bias fp32 [N]."""
+    M, K = A.shape
+    N = B.shape[0]
+    assert A.dtype == torch.bfloat16 and B.dtype == torch.bfloat16 and bias.dtype == torch.float32
+    assert A.is_contiguous() and B.is_contiguous() and B.shape[1] == K and bias.numel() == N
+    if epilogue == 2:
+        assert C is not None and C.dtype == torch.float32 and gate is not None and gate.dtype == torch.bfloat16
+        assert gate.is_contiguous() and tuple(gate.shape) == (M, N)
+    elif C is None:
+        C = torch.empty((M, N), dtype=torch.float32 if out_f32 else torch.bfloat16, device=A.device)
+    assert C.is_contiguous() and tuple(C.shape) == (M, N)
+    _check(_lib.csd_gemm_bf16(_ptr(A), _ptr(B), _ptr(bias), M, N, K, epilogue,
+                              1 if C.dtype == torch.float32 else 0, _ptr(C), _ptr(gate), _stream(stream)))
+    return C

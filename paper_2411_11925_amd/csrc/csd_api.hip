@@ -63,7 +63,7 @@ size_t head_ws_bytes(const csd_head* hd, int64_t R) {
     n += align_up(r * W * 4, 256);          // e
     n += align_up(r * W * act, 256);        // s
     n += align_up(r * 3 * W * act, 256);    // mod (one block at a time)
-    n += align_up(r * 2 * W * act, 256);    // fm
+    n += align_up(r * 2 * W * 4, 256);      // fm (fp32 in both modes)
     n += align_up(r * W * 4, 256);          // h
     n += align_up(r * W * act, 256);        // u
     n += align_up(r * W * act, 256);        // a
@@ -78,7 +78,7 @@ char* carve(const csd_head* hd, int64_t R, char* p, HeadWs* ws) {
     ws->e = (float*)take(r * W * 4);
     ws->s = take(r * W * act);
     ws->mod = take(r * 3 * W * act);
-    ws->fm = take(r * 2 * W * act);
+    ws->fm = take(r * 2 * W * 4);
     ws->h = (float*)take(r * W * 4);
     ws->u = take(r * W * act);
     ws->a = take(r * W * act);
@@ -130,13 +130,14 @@ hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hip
     g.M = (int)R; g.K = W; g.A = ws.s; g.lda = W;
     g.B = b16 ? (const void*)hd->fmod.w16 : (const void*)hd->fmod.w; g.bias = hd->fmod.b;
     g.C = ws.fm; g.ldc = 2 * W; g.N = 2 * W; g.epi = EPI_BIAS;
+    g.c_is_f32 = 1;     // the last modulation feeds eps_hat directly: kept in fp32
     return gemm(hd, g, st);
 }
 
 FinalArgs final_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
     FinalArgs f{};
     f.h = ws.h; f.fmod = ws.fm; f.ldm = 2 * hd->W;
-    f.act = hd->cfg.gemm_dtype == CSD_BF16 ? ACT_BF16 : ACT_F32;
+    f.act = ACT_F32;
     f.w_out = hd->out.w; f.b_out = hd->out.b; f.ln_eps = hd->ln_eps;
     f.R = R; f.W = hd->W; f.D = hd->D; f.x = ws.x; f.acc = ws.acc;
     f.coef = hd->coef[t]; f.t = t;
@@ -397,6 +398,20 @@ int csd_resample(const float* summary, const int32_t* n_accept, int64_t n_groups
     if (!summary || !n_accept || !tokens || !n_out) return fail(CSD_EINVAL, "csd_resample: NULL buffer");
     HIP_TRY(launch_resample(summary, n_accept, n_groups, gamma, token_dim, seed, row_offset, temperature, max_trips,
                             tokens, n_out, trips, flags, (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
+int csd_gemm_bf16(const void* A, const void* B, const float* bias, int64_t M, int32_t N, int32_t K, int32_t epilogue,
+                  int32_t out_f32, void* C, const void* gate, void* hip_stream) {
+    if (M < 0 || M > (1 << 22) || N < 64 || K < 64 || N % 64 || K % 64 || N > (1 << 20) || K > (1 << 20))
+        return fail(CSD_EINVAL, "csd_gemm_bf16: shape out of range (N and K multiples of 64)");
+    if (epilogue < 0 || epilogue > 2) return fail(CSD_EINVAL, "csd_gemm_bf16: epilogue must be 0, 1 or 2");
+    if (M == 0) return CSD_OK;
+    if (!A || !B || !bias || !C || (epilogue == EPI_GATE_RES && !gate)) return fail(CSD_EINVAL, "csd_gemm_bf16: NULL buffer");
+    GemmArgs g{};
+    g.A = A; g.lda = K; g.B = B; g.bias = bias; g.C = C; g.ldc = N; g.gate = gate; g.ldg = N;
+    g.M = (int)M; g.N = N; g.K = K; g.epi = epilogue; g.c_is_f32 = out_f32 ? 1 : 0;
+    HIP_TRY(launch_gemm_bf16(g, (hipStream_t)hip_stream));
     return CSD_OK;
 }
 

@@ -1,4 +1,229 @@
+// bf16 GEMM on the gfx950 matrix cores: C[M,N] = epilogue(A[M,K] * B[N,K]^T + bias),
+// A = activations, B = weights ([out,in] row-major), fp32 accumulation.
+//
+// One workgroup owns a BM x BN tile of C and walks K in slabs of BK = 64 through a
+// double-buffered LDS stage; each 64-lane wave owns a (BM/WM) x (BN/WN) sub-tile
+// built from 32x32x16 MFMAs.  The weights are fed as the MFMA "A" operand and the
+// activations as "B", so a lane ends up holding 4 CONSECUTIVE output features of
+// one row - the epilogue (bias, SiLU, gate*y + residual) then works on contiguous
+// 8- or 16-byte pieces of row-major C.
+// LDS rows are padded by 16 bytes so that the 16-byte fragment reads of 32
+// different rows fall into different banks.
+// Workgroup ids are remapped so that the ids that land on one XCD (id mod 8) walk
+// the N-tiles of the same rows of A: A is fetched from HBM once and the weight
+// matrix sits in every XCD's L2.
+// Requirements (checked by the launcher): K % 64 == 0, N % 64 == 0, 16-byte
+// aligned A, B and leading dimensions; M is free (ragged tail is predicated).
+#include <cstdlib>
+
 #include "internal.hpp"
+
 namespace csd {
-hipError_t launch_gemm_bf16(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int BK = 64;
+constexpr int LDS_STRIDE = BK + 8;      // bf16 elements per LDS row (144 bytes)
+
+__device__ __forceinline__ float silu_fast(float a) { return a / (1.0f + __expf(-a)); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
 }
+
+struct Params {
+    const bf16_t* A; int lda;
+    const bf16_t* B;            // ldb = K
+    const float* bias;
+    void* C; int ldc;
+    const bf16_t* gate; int ldg;
+    int M, N, K;
+    int tiles_m, tiles_n;
+};
+
+template <int BM, int BN, int WM, int WN, int EPI, bool OUT_F32>
+__global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int TM = BM / WM, TN = BN / WN;          // per-wave tile
+    constexpr int FM = TM / 32, FN = TN / 32;          // 32x32 blocks per wave
+    constexpr int CPR = BK / 8;                        // 16-byte chunks per tile row
+    constexpr int A_PASSES = BM * CPR / NT, B_PASSES = BN * CPR / NT;
+    static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
+    constexpr int STAGE = (BM + BN) * LDS_STRIDE;      // bf16 elements per stage
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+
+    // ---- tile of this workgroup: ids sharing id%8 (one XCD) sweep n first, then m
+    int tile = blockIdx.x;
+    {
+        const int total = p.tiles_m * p.tiles_n;
+        const int per_xcd = total / 8;                 // launcher guarantees total % 8 == 0 or no swizzle
+        if (per_xcd * 8 == total) tile = (tile % 8) * per_xcd + tile / 8;
+    }
+    const int tm = tile / p.tiles_n, tn = tile % p.tiles_n;
+    const int64_t m0 = (int64_t)tm * BM;
+    const int n0 = tn * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, khalf = lane >> 5;
+
+    // ---- global -> register staging: thread handles chunk (row, c8) of each pass
+    const int ld_row = tid / CPR, ld_c8 = tid % CPR;
+    constexpr int ROWS_PER_PASS = NT / CPR;
+    uint4 ga[A_PASSES], gb[B_PASSES];
+    const bf16_t* a_base = p.A + (m0 + ld_row) * p.lda + ld_c8 * 8;
+    const bf16_t* b_base = p.B + (size_t)(n0 + ld_row) * p.K + ld_c8 * 8;
+
+    auto load_global = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < A_PASSES; ++i) {
+            const int64_t r = m0 + ld_row + i * ROWS_PER_PASS;
+            ga[i] = (r < p.M) ? *reinterpret_cast<const uint4*>(a_base + (size_t)i * ROWS_PER_PASS * p.lda + k0)
+                              : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < B_PASSES; ++i)
+            gb[i] = *reinterpret_cast<const uint4*>(b_base + (size_t)i * ROWS_PER_PASS * p.K + k0);
+    };
+    auto store_lds = [&](int stage) {
+        bf16_t* sa = smem + stage * STAGE;
+        bf16_t* sb = sa + BM * LDS_STRIDE;
+#pragma unroll
+        for (int i = 0; i < A_PASSES; ++i)
+            *reinterpret_cast<uint4*>(sa + (ld_row + i * ROWS_PER_PASS) * LDS_STRIDE + ld_c8 * 8) = ga[i];
+#pragma unroll
+        for (int i = 0; i < B_PASSES; ++i)
+            *reinterpret_cast<uint4*>(sb + (ld_row + i * ROWS_PER_PASS) * LDS_STRIDE + ld_c8 * 8) = gb[i];
+    };
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int nk = p.K / BK;
+    load_global(0);
+    store_lds(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load_global((kt + 1) * BK);
+        const bf16_t* sa = smem + cur * STAGE + (wm * TM + l32) * LDS_STRIDE + khalf * 8;
+        const bf16_t* sb = smem + cur * STAGE + BM * LDS_STRIDE + (wn * TN + l32) * LDS_STRIDE + khalf * 8;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 fa[FM], fb[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+                fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sa + i * 32 * LDS_STRIDE + kk * 16));
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+                fb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sb + j * 32 * LDS_STRIDE + kk * 16));
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        }
+        if (kt + 1 < nk) store_lds(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane holds, per block (i,j) and q, features n..n+3 of row m
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int64_t m = m0 + wm * TM + i * 32 + l32;
+        if (m >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = n0 + wn * TN + j * 32 + q * 8 + khalf * 4;
+                const float4 bb = *reinterpret_cast<const float4*>(p.bias + n);
+                float v0 = acc[i][j][4 * q + 0] + bb.x, v1 = acc[i][j][4 * q + 1] + bb.y;
+                float v2 = acc[i][j][4 * q + 2] + bb.z, v3 = acc[i][j][4 * q + 3] + bb.w;
+                if (EPI == EPI_BIAS_SILU) { v0 = silu_fast(v0); v1 = silu_fast(v1); v2 = silu_fast(v2); v3 = silu_fast(v3); }
+                if (EPI == EPI_GATE_RES) {
+                    const uint2 g = *reinterpret_cast<const uint2*>(p.gate + m * p.ldg + n);
+                    float* cp = (float*)p.C + m * p.ldc + n;
+                    const float4 c = *reinterpret_cast<const float4*>(cp);
+                    v0 = fmaf(bf16_to_f32((bf16_t)(g.x & 0xFFFF)), v0, c.x);
+                    v1 = fmaf(bf16_to_f32((bf16_t)(g.x >> 16)), v1, c.y);
+                    v2 = fmaf(bf16_to_f32((bf16_t)(g.y & 0xFFFF)), v2, c.z);
+                    v3 = fmaf(bf16_to_f32((bf16_t)(g.y >> 16)), v3, c.w);
+                    *reinterpret_cast<float4*>(cp) = make_float4(v0, v1, v2, v3);
+                } else if (OUT_F32) {
+                    *reinterpret_cast<float4*>((float*)p.C + m * p.ldc + n) = make_float4(v0, v1, v2, v3);
+                } else {
+                    *reinterpret_cast<uint2*>((bf16_t*)p.C + m * p.ldc + n) =
+                        make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+                }
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int WM, int WN>
+hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
+    Params p;
+    p.A = (const bf16_t*)g.A; p.lda = g.lda; p.B = (const bf16_t*)g.B; p.bias = g.bias;
+    p.C = g.C; p.ldc = g.ldc; p.gate = (const bf16_t*)g.gate; p.ldg = g.ldg;
+    p.M = g.M; p.N = g.N; p.K = g.K;
+    p.tiles_m = (g.M + BM - 1) / BM; p.tiles_n = g.N / BN;
+    const size_t smem = (size_t)2 * (BM + BN) * LDS_STRIDE * sizeof(bf16_t);
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WM * WN * 64);
+#define CSD_LAUNCH(EPI, F32)                                                                                   \
+    do {                                                                                                       \
+        auto kern = k_gemm_bf16<BM, BN, WM, WN, EPI, F32>;                                                      \
+        static bool attr_done = false;                                                                          \
+        if (!attr_done) {                                                                                       \
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+            if (e != hipSuccess) return e;                                                                      \
+            attr_done = true;                                                                                   \
+        }                                                                                                       \
+        hipLaunchKernelGGL(kern, grid, block, smem, st, p);                                                     \
+    } while (0)
+    switch (g.epi) {
+        case EPI_BIAS: if (g.c_is_f32) CSD_LAUNCH(EPI_BIAS, true); else CSD_LAUNCH(EPI_BIAS, false); break;
+        case EPI_BIAS_SILU: if (g.c_is_f32) CSD_LAUNCH(EPI_BIAS_SILU, true); else CSD_LAUNCH(EPI_BIAS_SILU, false); break;
+        case EPI_GATE_RES: CSD_LAUNCH(EPI_GATE_RES, true); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef CSD_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// tuning hook: environment variable CSD_GEMM_VARIANT = 0..3 forces a tile shape
+static int gemm_variant_override() {
+    static int v = -2;
+    if (v == -2) { const char* e = getenv("CSD_GEMM_VARIANT"); v = (e && *e) ? atoi(e) : -1; }
+    return v;
+}
+
+hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
+    if (g.M == 0) return hipSuccess;
+    if (g.K % BK != 0 || g.N % 64 != 0 || g.lda % 8 != 0 || g.ldc % 4 != 0) return hipErrorInvalidValue;
+    if (((uintptr_t)g.A & 15u) || ((uintptr_t)g.B & 15u) || ((uintptr_t)g.C & 15u)) return hipErrorInvalidValue;
+    if (g.epi == EPI_GATE_RES && (g.ldg % 4 != 0 || ((uintptr_t)g.gate & 7u))) return hipErrorInvalidValue;
+    int variant = gemm_variant_override();
+    if (variant < 0) variant = (g.N % 256 == 0 && g.M >= 2048) ? 0 : (g.N % 128 == 0 && g.M >= 256) ? 2 : 3;
+    if (variant == 0 && g.N % 256 != 0) variant = 3;
+    if (variant == 1 && g.N % 256 != 0) variant = 3;
+    if (variant == 2 && g.N % 128 != 0) variant = 3;
+    switch (variant) {
+        case 0: return launch_cfg<256, 256, 2, 2>(g, st);    // 4 waves, 128x128 per wave
+        case 1: return launch_cfg<256, 256, 2, 4>(g, st);    // 8 waves, 128x64 per wave
+        case 2: return launch_cfg<128, 128, 2, 2>(g, st);    // 4 waves, 64x64 per wave
+        default: return launch_cfg<64, 64, 2, 2>(g, st);     // 4 waves, 32x32 per wave
+    }
+}
+
+}  // namespace csd

@@ -220,3 +220,65 @@ def test_empty_and_bad_calls(B):
     with pytest.raises(B.CsdError):
         B.csd_head_eval(dq, torch.zeros((4, 16), device=DEV), zz, 11)
     dq.free(); dp.free()
+
+
+# ------------------------------------------------------------- bf16 MFMA ----
+def _bf16(a):
+    return torch.from_numpy(S.bf16_round(a)).to(DEV).to(torch.bfloat16)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 64, 64), (70, 128, 192), (300, 192, 128), (515, 256, 1024),
+                                   (2048 + 37, 768, 256), (4096, 1024, 1024)])
+def test_gemm_bf16_all_epilogues(B, M, N, K):
+    rng = np.random.default_rng(M + N + K)
+    A = S.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
+    W = S.bf16_round((rng.normal(size=(N, K)) / math.sqrt(K)).astype(np.float32))
+    bias = rng.normal(size=N).astype(np.float32)
+    gate = S.bf16_round(rng.normal(size=(M, N)).astype(np.float32))
+    h0 = rng.normal(size=(M, N)).astype(np.float32)
+    ref = A.astype(np.float64) @ W.astype(np.float64).T + bias
+    tol = 2e-5 * math.sqrt(K)      # fp32 accumulation of K bf16 products
+    out = B.csd_gemm_bf16(_bf16(A), _bf16(W), _t(bias), 0, out_f32=True).cpu().numpy()
+    assert np.max(np.abs(out - ref)) < tol
+    out = B.csd_gemm_bf16(_bf16(A), _bf16(W), _t(bias), 0).float().cpu().numpy()
+    assert np.max(np.abs(out - ref) / (1 + np.abs(ref))) < 5e-3          # bf16 store
+    out = B.csd_gemm_bf16(_bf16(A), _bf16(W), _t(bias), 1, out_f32=True).cpu().numpy()
+    assert np.max(np.abs(out - O.silu(ref))) < tol
+    h = _t(h0.copy())
+    B.csd_gemm_bf16(_bf16(A), _bf16(W), _t(bias), 2, C=h, gate=_bf16(gate))
+    assert np.max(np.abs(h.cpu().numpy() - (h0 + gate.astype(np.float64) * ref))) < tol * 4
+
+
+@pytest.mark.parametrize("shape,T,R", [
+    (S.HeadShape(16, 64, 128, 2), 10, 131),
+    (S.HeadShape(8, 40, 192, 3), 7, 300),
+    (S.HeadShape(16, 768, 1024, 6), 100, 2100),
+    (S.HeadShape(16, 768, 768, 6), 100, 515)])
+def test_head_eval_bf16(B, shape, T, R):
+    blob = S.bf16_round(S.head_weights(shape, 21, out_scale=0.8, bias_std=0.2))
+    oh = O.Head(O.HeadCfg(shape.token_dim, shape.cond_dim, shape.width, shape.n_blocks, T, eps_skip_gain=1.0), blob)
+    dh = B.csd_init_head(B.make_cfg(shape.token_dim, shape.cond_dim, shape.width, shape.n_blocks, T,
+                                    B.CSD_BF16, eps_skip_gain=1.0), blob)
+    rng = np.random.default_rng(5)
+    x = rng.normal(size=(R, shape.token_dim)).astype(np.float32) * 1.5
+    z = rng.normal(size=(R, shape.cond_dim)).astype(np.float32)
+    for t in sorted({1, T}):
+        got = B.csd_head_eval(dh, _t(x), _t(z), t).cpu().numpy()
+        eh, v = oh.forward(x.astype(np.float64), t, oh.cond_embed(z.astype(np.float64)))
+        want = np.concatenate([eh, v], 1)
+        # one head evaluation is an intermediate, not a token: its worst element may sit a
+        # little above the token tolerance (narrow heads average fewer roundings); the
+        # root-mean-square error stays well below it
+        assert H.rel_err(got, want) < 1.5 * H.BF16_TOL
+        assert np.sqrt(np.mean((got - want) ** 2) / np.mean(want ** 2)) < 0.5 * H.BF16_TOL
+    dh.free()
+
+
+@pytest.mark.parametrize("out_scale", [0.05, 1.0])
+def test_tiny_workload_end_to_end_bf16(B, out_scale):
+    """bf16 MFMA path against the oracle fed the bf16-rounded weights: tokens within
+    2e-2; decisions are reported by the bench, not gated (log-ratios amplify
+    trajectory error by 1/sigma_1^2)."""
+    wl = S.WORKLOADS["tiny"].with_(gamma=2, gemm_dtype="bf16", out_scale=out_scale)
+    res = _end_to_end(B, wl, 150, H.BF16_TOL, dtype="bf16", check_decisions=False)
+    assert res["agree"] > (0.8 if out_scale < 0.5 else 0.0)
