@@ -1,0 +1,146 @@
+"""Benchmark of the hot path: verified tokens/s of denoise + verify + resample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mar256] [--dtype bf16]
+
+A step is one pass of the whole hot path (csd_denoise_lockstep, csd_verify,
+csd_resample) over all rows of the workload, inputs resident in HBM.  Prints one
+JSON line with the throughput, the roofline of the dominant kernel (the modulation
+GEMM, timed by hipEvents inside the timed region) and the fp64 oracle timed on a
+bounded row sample on the host cores.  One GPU only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"bf16": 2500.0, "f32": 157.3}     # MI355X dense peak, TFLOP/s
+
+
+def head_flops_per_row_step(sh):
+    W, L, D = sh.width, sh.n_blocks, sh.token_dim
+    return (10 * L + 4) * W * W + 6 * D * W
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="mar256")
+    ap.add_argument("--dtype", default=None, choices=[None, "bf16", "f32"])
+    ap.add_argument("--rows", type=int, default=0, help="rows per step (default: the whole workload)")
+    ap.add_argument("--oracle-rows", type=int, default=128, help="rows of the CPU-oracle sample (0: skip)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py measures one GPU: every box of this build has one MI355X and the path has no "
+                 "cross-GPU step (rows shard by group with replicated weights); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2411_11925_amd import binding as B
+    from paper_2411_11925_amd import synth as S
+
+    wl = S.WORKLOADS[a.workload]
+    dtype = a.dtype or wl.gemm_dtype
+    wl = wl.with_(gemm_dtype=dtype)
+    R = a.rows or wl.rows_total
+    gamma, D = wl.gamma, wl.target.token_dim
+    G = R // gamma
+    R = G * gamma
+    dev = "cuda:0"
+    tb, db, ds = wl.heads()
+    gd = B.CSD_BF16 if dtype == "bf16" else B.CSD_F32
+    mk = lambda sh: B.make_cfg(sh.token_dim, sh.cond_dim, sh.width, sh.n_blocks, wl.n_steps, gd,
+                               eps_skip_gain=wl.eps_skip_gain)
+    h_q, h_p = B.csd_init_head(mk(ds), db), B.csd_init_head(mk(wl.target), tb)
+    zq_h, zp_h = wl.conds(((R + 63) // 64) * 64)
+    z_q, z_p = torch.from_numpy(zq_h[:R]).to(dev), torch.from_numpy(zp_h[:R]).to(dev)
+    ws = torch.empty(B.csd_workspace_bytes(h_q, h_p, R), dtype=torch.uint8, device=dev)
+    summary = torch.empty((R, 5 * D + 1), dtype=torch.float32, device=dev)
+
+    def step():
+        B.csd_denoise_lockstep(h_q, h_p, z_q, z_p, G, gamma, wl.seed, 0, 1.0, summary, ws)
+        n_acc, ell, mask = B.csd_verify(summary, G, gamma, D, wl.seed)
+        out = B.csd_resample(summary, n_acc, G, gamma, D, wl.seed)
+        return n_acc, ell, mask, out
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    launches_per_step = 2 * wl.n_steps * (ds.n_blocks + wl.target.n_blocks) // 2
+    B.csd_profile_enable(min(a.steps * launches_per_step + 16, 1 << 18))
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(a.steps):
+        n_acc, ell, mask, (tokens, n_out, trips, flags) = step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = ev0.elapsed_time(ev1)
+    k_ms, k_n, k_flops = B.csd_profile_read()
+    B.csd_profile_enable(0)
+
+    flops_row = wl.n_steps * (head_flops_per_row_step(wl.target) + head_flops_per_row_step(ds)) \
+        + 2 * wl.target.cond_dim * (wl.target.width + ds.width)
+    tokens_per_s = R * a.steps / (ms / 1e3)
+    achieved = (k_flops / k_n) / (k_ms / k_n / 1e3) / 1e12 if k_n else 0.0
+    peak = PEAK[dtype]
+    mask_h, trips_h, nacc_h = mask.cpu().numpy(), trips.cpu().numpy(), n_acc.cpu().numpy()
+    res = {
+        "metric": "verified tokens/sec (denoise+verify+resample)", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms / a.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": "%s: target %dx%d, draft %dx%d, C=%d, T=%d, rows/step=%d (G=%d, gamma=%d)" % (
+            wl.name, wl.target.n_blocks, wl.target.width, ds.n_blocks, ds.width, wl.target.cond_dim,
+            wl.n_steps, R, G, gamma), "rows_per_step": R, "gamma": gamma, "out_scale": wl.out_scale,
+            "eps_skip_gain": wl.eps_skip_gain},
+        "wall_s": wall,
+        "whole_path": {"algorithmic_TFLOP_per_s": flops_row * R * a.steps / (ms / 1e3) / 1e12,
+                       "frac_of_peak": flops_row * R * a.steps / (ms / 1e3) / 1e12 / peak,
+                       "GFLOP_per_row": flops_row / 1e9},
+        "acceptance": {"row_accept_rate": float(mask_h.mean()), "mean_accepted_prefix": float(nacc_h.mean()),
+                       "resample_trips_mean": float(trips_h[trips_h > 0].mean()) if (trips_h > 0).any() else 0.0,
+                       "resample_trips_max": int(trips_h.max()), "cap_flags": int((flags.cpu().numpy() & 1).sum())},
+        "roofline": {"bound": "mfma" if dtype == "bf16" else "alu", "kernel": "modulation GEMM [R,W]x[W,3W]",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "launches_timed": k_n, "avg_launch_ms": k_ms / k_n if k_n else None, "traffic": None},
+    }
+
+    if a.oracle_rows > 0:
+        from oracle import csd_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        n = min(a.oracle_rows // gamma * gamma, R)
+        ocfg = lambda sh: O.HeadCfg(sh.token_dim, sh.cond_dim, sh.width, sh.n_blocks, wl.n_steps,
+                                    eps_skip_gain=wl.eps_skip_gain)
+        t0 = time.perf_counter()
+        o_q, o_p = O.Head(ocfg(ds), db), O.Head(ocfg(wl.target), tb)
+        t_init = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        s_o, _ = O.denoise_lockstep(o_q, o_p, zq_h[:n], zp_h[:n], wl.seed)
+        n_o, ell_o, mask_o, log_u = O.verify(s_o, n // gamma, gamma, wl.seed)
+        O.resample(s_o, n_o, n // gamma, gamma, wl.seed)
+        dt = time.perf_counter() - t0
+        x_g, x_o = summary[:n].cpu().numpy()[:, 4 * D:5 * D], s_o[:, 4 * D:5 * D]
+        clear = np.abs(log_u - ell_o) >= 1e-3
+        res["cpu_baseline"] = {"value": n / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": "first %d rows of the same workload, fp64 numpy oracle, %.1f s "
+                                         "(+%.1f s set-up)" % (n, dt, t_init)}
+        res["parity_on_sample"] = {
+            "rows": n, "token_max_err_over_rms": float(np.max(np.abs(x_g - x_o)) / np.sqrt(np.mean(x_o ** 2))),
+            "decision_agreement": float((mask_h[:n].astype(bool) == (log_u <= ell_o)).mean()),
+            "decision_agreement_outside_band": float((mask_h[:n].astype(bool) == (log_u <= ell_o))[clear].mean()),
+            "oracle_row_accept_rate": float(mask_o.mean())}
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -207,6 +207,18 @@ int csd_rng_uniforms(uint64_t seed, uint64_t row_offset, int64_t n_rows, int32_t
 int csd_gemm_bf16(const void* A, const void* B, const float* bias, int64_t M, int32_t N, int32_t K,
                   int32_t epilogue, int32_t out_f32, void* C, const void* gate, void* hip_stream);
 
+/*
+ * Timing of the dominant kernel (the modulation GEMM of csd_denoise_lockstep).
+ * While enabled, every launch of that kernel is bracketed by two hipEvents on its
+ * launch stream (up to `max_launches`; later launches run untimed).
+ * csd_profile_read waits for the recorded events and returns the sum of the
+ * kernel durations in milliseconds, the number of launches timed and the sum of
+ * their algorithmic flops (2*M*N*K each); it then clears the record.
+ * csd_profile_enable(0) stops recording and frees the events.
+ */
+int csd_profile_enable(int32_t max_launches);
+int csd_profile_read(double* ms_sum, int64_t* launches, double* flops_sum);
+
 /* Message of the last failing call on this thread ("" if none). */
 const char* csd_last_error(void);
 

@@ -30,7 +30,7 @@ CSD_FLAG_CAP, CSD_FLAG_NONFINITE = 1, 2
 
 EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_workspace_bytes",
            "csd_denoise_lockstep", "csd_verify", "csd_resample", "csd_head_eval",
-           "csd_rng_normals", "csd_rng_uniforms", "csd_gemm_bf16", "csd_last_error"]
+           "csd_rng_normals", "csd_rng_uniforms", "csd_gemm_bf16", "csd_profile_enable", "csd_profile_read", "csd_last_error"]
 
 
 class csd_head_cfg_t(Structure):
@@ -72,6 +72,12 @@ _lib.csd_rng_uniforms.argtypes = [c_uint64, c_uint64, c_int64, c_int32, c_int32,
 _lib.csd_gemm_bf16.restype = c_int
 _lib.csd_gemm_bf16.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_int32, c_int32,
                                c_void_p, c_void_p, c_void_p]
+
+
+_lib.csd_profile_enable.restype = c_int
+_lib.csd_profile_enable.argtypes = [c_int32]
+_lib.csd_profile_read.restype = c_int
+_lib.csd_profile_read.argtypes = [POINTER(c_double), POINTER(c_int64), POINTER(c_double)]
 
 
 class CsdError(RuntimeError):
@@ -248,3 +254,14 @@ def csd_gemm_bf16(A: torch.Tensor, B: torch.Tensor, bias: torch.Tensor, epilogue
     _check(_lib.csd_gemm_bf16(_ptr(A), _ptr(B), _ptr(bias), M, N, K, epilogue,
                               1 if C.dtype == torch.float32 else 0, _ptr(C), _ptr(gate), _stream(stream)))
     return C
+
+
+def csd_profile_enable(max_launches: int):
+    _check(_lib.csd_profile_enable(max_launches))
+
+
+def csd_profile_read():
+    """(sum of kernel milliseconds, launches timed, sum of algorithmic flops)."""
+    ms, n, fl = c_double(), c_int64(), c_double()
+    _check(_lib.csd_profile_read(byref(ms), byref(n), byref(fl)))
+    return ms.value, n.value, fl.value

@@ -91,6 +91,26 @@ hipError_t gemm(const csd_head* hd, GemmArgs g, hipStream_t st) {
     return hd->cfg.gemm_dtype == CSD_BF16 ? launch_gemm_bf16(g, st) : launch_gemm_f32(g, st);
 }
 
+// optional hipEvent bracket around the dominant kernel (csd_profile_*)
+struct Profile {
+    std::vector<hipEvent_t> ev;     // 2 per launch
+    std::vector<double> flops;
+    size_t used = 0;                // launches recorded
+    bool on = false;
+} g_prof;
+
+hipError_t gemm_timed(const csd_head* hd, const GemmArgs& g, hipStream_t st) {
+    if (!g_prof.on || g_prof.used * 2 + 2 > g_prof.ev.size()) return gemm(hd, g, st);
+    const size_t i = g_prof.used;
+    hipError_t e = hipEventRecord(g_prof.ev[2 * i], st);
+    if (e != hipSuccess) return e;
+    if ((e = gemm(hd, g, st)) != hipSuccess) return e;
+    if ((e = hipEventRecord(g_prof.ev[2 * i + 1], st)) != hipSuccess) return e;
+    g_prof.flops.push_back(2.0 * g.M * g.N * g.K);
+    g_prof.used = i + 1;
+    return hipSuccess;
+}
+
 // e = W_c z + b_c (once per call; fp32 in both modes)
 hipError_t cond_embed(const csd_head* hd, const float* z, const HeadWs& ws, int64_t R, hipStream_t st) {
     GemmArgs g{};
@@ -114,7 +134,7 @@ hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hip
         // (shift, scale, gate) = Lin_mod(s)
         g.A = ws.s; g.lda = W; g.B = b16 ? (const void*)hd->mod[l].w16 : (const void*)hd->mod[l].w;
         g.bias = hd->mod[l].b; g.C = ws.mod; g.ldc = 3 * W; g.N = 3 * W; g.epi = EPI_BIAS;
-        if ((e = gemm(hd, g, st)) != hipSuccess) return e;
+        if ((e = gemm_timed(hd, g, st)) != hipSuccess) return e;
         if ((e = launch_ln_mod(ws.h, ws.mod, 3 * W, ws.u, act, hd->ln_eps, R, W, st)) != hipSuccess) return e;
         // a = silu(fc1 u)
         g.A = ws.u; g.B = b16 ? (const void*)hd->fc1[l].w16 : (const void*)hd->fc1[l].w;
@@ -398,6 +418,38 @@ int csd_resample(const float* summary, const int32_t* n_accept, int64_t n_groups
     if (!summary || !n_accept || !tokens || !n_out) return fail(CSD_EINVAL, "csd_resample: NULL buffer");
     HIP_TRY(launch_resample(summary, n_accept, n_groups, gamma, token_dim, seed, row_offset, temperature, max_trips,
                             tokens, n_out, trips, flags, (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
+int csd_profile_enable(int32_t max_launches) {
+    for (hipEvent_t ev : g_prof.ev) (void)hipEventDestroy(ev);
+    g_prof.ev.clear(); g_prof.flops.clear(); g_prof.used = 0; g_prof.on = false;
+    if (max_launches <= 0) return CSD_OK;
+    if (max_launches > (1 << 20)) return fail(CSD_EINVAL, "csd_profile_enable: at most 2^20 launches");
+    g_prof.ev.resize((size_t)max_launches * 2);
+    for (size_t i = 0; i < g_prof.ev.size(); ++i) {
+        hipError_t e = hipEventCreate(&g_prof.ev[i]);
+        if (e != hipSuccess) {
+            for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(g_prof.ev[j]);
+            g_prof.ev.clear();
+            return fail(CSD_EHIP, "csd_profile_enable: hipEventCreate: %s", hipGetErrorString(e));
+        }
+    }
+    g_prof.on = true;
+    return CSD_OK;
+}
+
+int csd_profile_read(double* ms_sum, int64_t* launches, double* flops_sum) {
+    if (!ms_sum || !launches || !flops_sum) return fail(CSD_EINVAL, "csd_profile_read: NULL output");
+    double ms = 0.0, fl = 0.0;
+    for (size_t i = 0; i < g_prof.used; ++i) {
+        HIP_TRY(hipEventSynchronize(g_prof.ev[2 * i + 1]));
+        float t = 0.f;
+        HIP_TRY(hipEventElapsedTime(&t, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]));
+        ms += t; fl += g_prof.flops[i];
+    }
+    *ms_sum = ms; *launches = (int64_t)g_prof.used; *flops_sum = fl;
+    g_prof.used = 0; g_prof.flops.clear();
     return CSD_OK;
 }
 

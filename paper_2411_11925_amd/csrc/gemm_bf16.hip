@@ -1,19 +1,25 @@
 // bf16 GEMM on the gfx950 matrix cores: C[M,N] = epilogue(A[M,K] * B[N,K]^T + bias),
 // A = activations, B = weights ([out,in] row-major), fp32 accumulation.
 //
-// One workgroup owns a BM x BN tile of C and walks K in slabs of BK = 64 through a
-// double-buffered LDS stage; each 64-lane wave owns a (BM/WM) x (BN/WN) sub-tile
-// built from 32x32x16 MFMAs.  The weights are fed as the MFMA "A" operand and the
-// activations as "B", so a lane ends up holding 4 CONSECUTIVE output features of
-// one row - the epilogue (bias, SiLU, gate*y + residual) then works on contiguous
-// 8- or 16-byte pieces of row-major C.
-// LDS rows are padded by 16 bytes so that the 16-byte fragment reads of 32
-// different rows fall into different banks.
+// One workgroup owns a BM x BN tile of C and walks K in slabs of BK = 64.  Each slab
+// of A and B goes from global memory STRAIGHT INTO LDS (global_load_lds, 16 bytes per
+// lane, no staging registers), double-buffered: the loads of slab k+1 are in flight
+// while the MFMAs of slab k run, and one barrier per slab separates the two.
+// A direct load writes 64 lanes x 16 bytes contiguously, i.e. 8 LDS rows of 128 bytes,
+// so rows cannot be padded; bank conflicts of the fragment reads (32 rows, one 16-byte
+// chunk each) are avoided by an XOR swizzle instead: logical chunk c of row r lives at
+// chunk c ^ ((r >> 1) & 7).  The swizzle is applied on the global-address side of the
+// load (lane l fetches the logical chunk that belongs at its fixed LDS position).
+// Each 64-lane wave owns a (BM/WM) x (BN/WN) sub-tile built from 32x32x16 MFMAs.  The
+// weights are fed as the MFMA "A" operand and the activations as "B", so a lane ends
+// up holding 4 CONSECUTIVE output features of one row - the epilogue (bias, SiLU,
+// gate*y + residual) then works on contiguous 8- or 16-byte pieces of row-major C.
 // Workgroup ids are remapped so that the ids that land on one XCD (id mod 8) walk
 // the N-tiles of the same rows of A: A is fetched from HBM once and the weight
 // matrix sits in every XCD's L2.
 // Requirements (checked by the launcher): K % 64 == 0, N % 64 == 0, 16-byte
-// aligned A, B and leading dimensions; M is free (ragged tail is predicated).
+// aligned A, B and leading dimensions; M is free (rows past M are clamped on load
+// and never stored).
 #include <cstdlib>
 
 #include "internal.hpp"
@@ -26,13 +32,9 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int BK = 64;
-constexpr int LDS_STRIDE = BK + 8;      // bf16 elements per LDS row (144 bytes)
+constexpr int ROW_B = BK * 2;           // bytes per LDS row
 
 __device__ __forceinline__ float silu_fast(float a) { return a / (1.0f + __expf(-a)); }
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-}
 
 struct Params {
     const bf16_t* A; int lda;
@@ -46,20 +48,20 @@ struct Params {
 
 template <int BM, int BN, int WM, int WN, int EPI, bool OUT_F32>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
-    constexpr int NT = WM * WN * 64;
+    constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;          // per-wave tile
     constexpr int FM = TM / 32, FN = TN / 32;          // 32x32 blocks per wave
-    constexpr int CPR = BK / 8;                        // 16-byte chunks per tile row
-    constexpr int A_PASSES = BM * CPR / NT, B_PASSES = BN * CPR / NT;
-    static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
-    constexpr int STAGE = (BM + BN) * LDS_STRIDE;      // bf16 elements per stage
-    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    constexpr int GROUPS = (BM + BN) / 8;              // 8-row groups (1 KiB of LDS) per stage
+    constexpr int GPW = GROUPS / NW;                   // groups loaded by each wave
+    static_assert(GROUPS % NW == 0 && NW % 2 == 0 && (BM / 8) % 2 == 0, "loader mapping");
+    constexpr int STAGE_B = (BM + BN) * ROW_B;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // ---- tile of this workgroup: ids sharing id%8 (one XCD) sweep n first, then m
     int tile = blockIdx.x;
     {
         const int total = p.tiles_m * p.tiles_n;
-        const int per_xcd = total / 8;                 // launcher guarantees total % 8 == 0 or no swizzle
+        const int per_xcd = total / 8;
         if (per_xcd * 8 == total) tile = (tile % 8) * per_xcd + tile / 8;
     }
     const int tm = tile / p.tiles_n, tn = tile % p.tiles_n;
@@ -70,34 +72,34 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, khalf = lane >> 5;
 
-    // ---- global -> register staging: thread handles chunk (row, c8) of each pass
-    const int ld_row = tid / CPR, ld_c8 = tid % CPR;
-    constexpr int ROWS_PER_PASS = NT / CPR;
-    uint4 ga[A_PASSES], gb[B_PASSES];
-    const bf16_t* a_base = p.A + (m0 + ld_row) * p.lda + ld_c8 * 8;
-    const bf16_t* b_base = p.B + (size_t)(n0 + ld_row) * p.K + ld_c8 * 8;
-
-    auto load_global = [&](int k0) {
+    // ---- loader: lane (lr, pc) of a group writes LDS row lr, physical chunk pc
+    const int lr = lane >> 3, pc = lane & 7;
+    const int ld_chunk = pc ^ ((((wave & 1) << 2) + (lr >> 1)) & 7);   // logical chunk to fetch
+    auto issue_loads = [&](int stage, int k0) {
 #pragma unroll
-        for (int i = 0; i < A_PASSES; ++i) {
-            const int64_t r = m0 + ld_row + i * ROWS_PER_PASS;
-            ga[i] = (r < p.M) ? *reinterpret_cast<const uint4*>(a_base + (size_t)i * ROWS_PER_PASS * p.lda + k0)
-                              : make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < GPW; ++i) {
+            const int g = wave + i * NW;               // group index: rows 8g .. 8g+7 of the stage
+            const int row = g * 8 + lr;
+            const bf16_t* src;
+            if (g < BM / 8) {                          // uniform per wave and i
+                int64_t r = m0 + row;
+                r = r < p.M ? r : (int64_t)p.M - 1;
+                src = p.A + r * p.lda + k0 + ld_chunk * 8;
+            } else {
+                src = p.B + (size_t)(n0 + row - BM) * p.K + k0 + ld_chunk * 8;
+            }
+            __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void*)(smem + stage * STAGE_B + g * 1024),
+                                             16, 0, 0);
         }
-#pragma unroll
-        for (int i = 0; i < B_PASSES; ++i)
-            gb[i] = *reinterpret_cast<const uint4*>(b_base + (size_t)i * ROWS_PER_PASS * p.K + k0);
     };
-    auto store_lds = [&](int stage) {
-        bf16_t* sa = smem + stage * STAGE;
-        bf16_t* sb = sa + BM * LDS_STRIDE;
+
+    // ---- fragment read offsets (bytes) of this lane for the 4 k16-steps of a slab
+    const int swz = (l32 >> 1) & 7;
+    int koff[BK / 16];
 #pragma unroll
-        for (int i = 0; i < A_PASSES; ++i)
-            *reinterpret_cast<uint4*>(sa + (ld_row + i * ROWS_PER_PASS) * LDS_STRIDE + ld_c8 * 8) = ga[i];
-#pragma unroll
-        for (int i = 0; i < B_PASSES; ++i)
-            *reinterpret_cast<uint4*>(sb + (ld_row + i * ROWS_PER_PASS) * LDS_STRIDE + ld_c8 * 8) = gb[i];
-    };
+    for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = ((kk * 2 + khalf) ^ swz) * 16;
+    const int a_row_off = (wm * TM + l32) * ROW_B;
+    const int b_row_off = (BM + wn * TN + l32) * ROW_B;
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -108,30 +110,30 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
     const int nk = p.K / BK;
-    load_global(0);
-    store_lds(0);
+    issue_loads(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): this wave's direct loads have landed
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
-        const bf16_t* sa = smem + cur * STAGE + (wm * TM + l32) * LDS_STRIDE + khalf * 8;
-        const bf16_t* sb = smem + cur * STAGE + BM * LDS_STRIDE + (wn * TN + l32) * LDS_STRIDE + khalf * 8;
+        if (kt + 1 < nk) issue_loads(cur ^ 1, (kt + 1) * BK);
+        const unsigned char* sa = smem + cur * STAGE_B + a_row_off;
+        const unsigned char* sb = smem + cur * STAGE_B + b_row_off;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 fa[FM], fb[FN];
 #pragma unroll
             for (int i = 0; i < FM; ++i)
-                fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sa + i * 32 * LDS_STRIDE + kk * 16));
+                fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sa + i * 32 * ROW_B + koff[kk]));
 #pragma unroll
             for (int j = 0; j < FN; ++j)
-                fb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sb + j * 32 * LDS_STRIDE + kk * 16));
+                fb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sb + j * 32 * ROW_B + koff[kk]));
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) store_lds(cur ^ 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
     }
 
@@ -176,7 +178,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     p.C = g.C; p.ldc = g.ldc; p.gate = (const bf16_t*)g.gate; p.ldg = g.ldg;
     p.M = g.M; p.N = g.N; p.K = g.K;
     p.tiles_m = (g.M + BM - 1) / BM; p.tiles_n = g.N / BN;
-    const size_t smem = (size_t)2 * (BM + BN) * LDS_STRIDE * sizeof(bf16_t);
+    const size_t smem = (size_t)2 * (BM + BN) * ROW_B;
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WM * WN * 64);
 #define CSD_LAUNCH(EPI, F32)                                                                                   \
     do {                                                                                                       \
@@ -199,14 +201,14 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     return hipGetLastError();
 }
 
-}  // namespace
-
 // tuning hook: environment variable CSD_GEMM_VARIANT = 0..3 forces a tile shape
-static int gemm_variant_override() {
+int gemm_variant_override() {
     static int v = -2;
     if (v == -2) { const char* e = getenv("CSD_GEMM_VARIANT"); v = (e && *e) ? atoi(e) : -1; }
     return v;
 }
+
+}  // namespace
 
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
     if (g.M == 0) return hipSuccess;
@@ -214,9 +216,8 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
     if (((uintptr_t)g.A & 15u) || ((uintptr_t)g.B & 15u) || ((uintptr_t)g.C & 15u)) return hipErrorInvalidValue;
     if (g.epi == EPI_GATE_RES && (g.ldg % 4 != 0 || ((uintptr_t)g.gate & 7u))) return hipErrorInvalidValue;
     int variant = gemm_variant_override();
-    if (variant < 0) variant = (g.N % 256 == 0 && g.M >= 2048) ? 0 : (g.N % 128 == 0 && g.M >= 256) ? 2 : 3;
-    if (variant == 0 && g.N % 256 != 0) variant = 3;
-    if (variant == 1 && g.N % 256 != 0) variant = 3;
+    if (variant < 0) variant = (g.N % 256 == 0 && g.M >= 2048) ? 1 : (g.N % 128 == 0 && g.M >= 256) ? 2 : 3;
+    if ((variant == 0 || variant == 1) && g.N % 256 != 0) variant = 3;
     if (variant == 2 && g.N % 128 != 0) variant = 3;
     switch (variant) {
         case 0: return launch_cfg<256, 256, 2, 2>(g, st);    // 4 waves, 128x128 per wave

@@ -14,12 +14,20 @@ typedef uint16_t bf16_t;   // storage only; conversions below
 __host__ __device__ inline float bf16_to_f32(bf16_t v) {
     union { uint32_t u; float f; } c; c.u = (uint32_t)v << 16; return c.f;
 }
-// round to nearest even (NaN keeps a quiet payload bit)
-__host__ __device__ inline bf16_t f32_to_bf16(float f) {
-    union { uint32_t u; float f; } c; c.f = f;
-    if ((c.u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((c.u >> 16) | 0x40u);
-    return (bf16_t)((c.u + 0x7FFFu + ((c.u >> 16) & 1u)) >> 16);
+// round to nearest even; on the device this is the hardware conversion of gfx950
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__host__ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));   // v_cvt_pk_bf16_f32
+#else
+    union { uint32_t u; float f; } a, b; a.f = lo; b.f = hi;
+    const uint32_t ra = (a.u + 0x7FFFu + ((a.u >> 16) & 1u)) >> 16, rb = (b.u + 0x7FFFu + ((b.u >> 16) & 1u)) >> 16;
+    return (ra & 0xFFFFu) | (rb << 16);
+#endif
 }
+__host__ __device__ inline bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16x2(f, 0.f) & 0xFFFFu); }
 
 // per-step constants of one head's sampler, fp32 copies of host doubles
 struct StepCoef {
