@@ -54,7 +54,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // device buffers of one head for R rows, carved from the caller's workspace
 struct HeadWs {
-    float* e; void* s; void* mod; void* fm; float* h; void* u; void* a; float* x; float* acc;
+    float* e; void* s; void* mod; float* fm; float* h; void* u; void* a; float* o; float* x; float* acc;
 };
 
 size_t head_ws_bytes(const csd_head* hd, int64_t R) {
@@ -65,8 +65,9 @@ size_t head_ws_bytes(const csd_head* hd, int64_t R) {
     n += align_up(r * 3 * W * act, 256);    // mod (one block at a time)
     n += align_up(r * 2 * W * 4, 256);      // fm (fp32 in both modes)
     n += align_up(r * W * 4, 256);          // h
-    n += align_up(r * W * act, 256);        // u
+    n += align_up(r * W * 4, 256);          // u (fp32, bf16, or the [hi|lo] bf16 pair of the last layer)
     n += align_up(r * W * act, 256);        // a
+    n += align_up(r * 64 * 4, 256);         // o (output projection, padded to 64 columns)
     n += align_up(r * hd->D * 4, 256);      // x
     n += align_up(r * 4, 256);              // acc
     return n;
@@ -78,10 +79,11 @@ char* carve(const csd_head* hd, int64_t R, char* p, HeadWs* ws) {
     ws->e = (float*)take(r * W * 4);
     ws->s = take(r * W * act);
     ws->mod = take(r * 3 * W * act);
-    ws->fm = take(r * 2 * W * 4);
+    ws->fm = (float*)take(r * 2 * W * 4);
     ws->h = (float*)take(r * W * 4);
-    ws->u = take(r * W * act);
+    ws->u = take(r * W * 4);
     ws->a = take(r * W * act);
+    ws->o = (float*)take(r * 64 * 4);
     ws->x = (float*)take(r * hd->D * 4);
     ws->acc = (float*)take(r * 4);
     return p;
@@ -135,7 +137,7 @@ hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hip
         g.A = ws.s; g.lda = W; g.B = b16 ? (const void*)hd->mod[l].w16 : (const void*)hd->mod[l].w;
         g.bias = hd->mod[l].b; g.C = ws.mod; g.ldc = 3 * W; g.N = 3 * W; g.epi = EPI_BIAS;
         if ((e = gemm_timed(hd, g, st)) != hipSuccess) return e;
-        if ((e = launch_ln_mod(ws.h, ws.mod, 3 * W, ws.u, act, hd->ln_eps, R, W, st)) != hipSuccess) return e;
+        if ((e = launch_ln_mod(ws.h, ws.mod, 3 * W, b16 ? 0 : 1, ws.u, b16 ? LN_OUT_BF16 : LN_OUT_F32, hd->ln_eps, R, W, st)) != hipSuccess) return e;
         // a = silu(fc1 u)
         g.A = ws.u; g.B = b16 ? (const void*)hd->fc1[l].w16 : (const void*)hd->fc1[l].w;
         g.bias = hd->fc1[l].b; g.C = ws.a; g.ldc = W; g.N = W; g.epi = EPI_BIAS_SILU;
@@ -151,15 +153,20 @@ hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hip
     g.B = b16 ? (const void*)hd->fmod.w16 : (const void*)hd->fmod.w; g.bias = hd->fmod.b;
     g.C = ws.fm; g.ldc = 2 * W; g.N = 2 * W; g.epi = EPI_BIAS;
     g.c_is_f32 = 1;     // the last modulation feeds eps_hat directly: kept in fp32
-    return gemm(hd, g, st);
+    if ((e = gemm(hd, g, st)) != hipSuccess) return e;
+    // o = Lin_out(LN(h)*(1+scale)+shift), padded to 64 columns.  In bf16 mode the input goes
+    // in as a [hi | lo] bf16 pair against [w | w], i.e. with fp32-like accuracy.
+    if ((e = launch_ln_mod(ws.h, ws.fm, 2 * W, 1, ws.u, b16 ? LN_OUT_BF16_SPLIT : LN_OUT_F32, hd->ln_eps, R, W, st)) != hipSuccess) return e;
+    GemmArgs go{};
+    go.M = (int)R; go.N = 64; go.K = b16 ? 2 * W : W; go.A = ws.u; go.lda = go.K;
+    go.B = b16 ? (const void*)hd->out_pad.w16 : (const void*)hd->out_pad.w; go.bias = hd->out_pad.b;
+    go.C = ws.o; go.ldc = 64; go.epi = EPI_BIAS; go.c_is_f32 = 1;
+    return gemm(hd, go, st);
 }
 
-FinalArgs final_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
-    FinalArgs f{};
-    f.h = ws.h; f.fmod = ws.fm; f.ldm = 2 * hd->W;
-    f.act = ACT_F32;
-    f.w_out = hd->out.w; f.b_out = hd->out.b; f.ln_eps = hd->ln_eps;
-    f.R = R; f.W = hd->W; f.D = hd->D; f.x = ws.x; f.acc = ws.acc;
+TransArgs trans_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
+    TransArgs f{};
+    f.o = ws.o; f.ldo = 64; f.R = R; f.D = hd->D; f.x = ws.x; f.acc = ws.acc;
     f.coef = hd->coef[t]; f.t = t;
     return f;
 }
@@ -189,6 +196,7 @@ void csd_free_head(csd_head_t* h) {
     if (h->d_weights) (void)hipFree(h->d_weights);
     if (h->d_weights16) (void)hipFree(h->d_weights16);
     if (h->d_time_emb) (void)hipFree(h->d_time_emb);
+    if (h->d_out_pad) (void)hipFree(h->d_out_pad);
     delete h;
 }
 
@@ -279,6 +287,16 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
     lin(h->fmod, 2 * W, W, true);
     lin(h->out, 2 * D, W, false);
     if (off != n_floats) return bail(fail(CSD_EINVAL, "csd_init_head: internal layout mismatch"));
+    // output layer padded with zero rows to 64 outputs, so that it runs through the GEMM kernels
+    {
+        const size_t nw = (size_t)64 * W;
+        INIT_TRY(hipMalloc((void**)&h->d_out_pad, (nw + 64) * sizeof(float)));
+        INIT_TRY(hipMemset(h->d_out_pad, 0, (nw + 64) * sizeof(float)));
+        INIT_TRY(hipMemcpy(h->d_out_pad, h->out.w, (size_t)2 * D * W * sizeof(float), hipMemcpyDeviceToDevice));
+        INIT_TRY(hipMemcpy(h->d_out_pad + nw, h->out.b, (size_t)2 * D * sizeof(float), hipMemcpyDeviceToDevice));
+        h->out_pad.w = h->d_out_pad; h->out_pad.b = h->d_out_pad + nw; h->out_pad.n_out = 64; h->out_pad.n_in = W;
+        if (b16) n16 += 2 * nw;
+    }
     if (b16) {
         INIT_TRY(hipMalloc((void**)&h->d_weights16, n16 * sizeof(bf16_t)));
         size_t o16 = 0;
@@ -287,6 +305,11 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
             INIT_TRY(launch_f32_to_bf16(l->w, h->d_weights16 + o16, n, nullptr));
             l->w16 = h->d_weights16 + o16; o16 += n;
         }
+        // [w | w]: row o of the bf16 output layer holds its W weights twice
+        bf16_t* dst = h->d_weights16 + o16;
+        INIT_TRY(launch_f32_to_bf16_rows(h->out_pad.w, dst, 64, W, 2 * W, nullptr));
+        INIT_TRY(launch_f32_to_bf16_rows(h->out_pad.w, dst + W, 64, W, 2 * W, nullptr));
+        h->out_pad.w16 = dst;
     }
 
     // ---- time embedding table E_t[t], t = 1..T: sinusoidal features in double on the
@@ -358,10 +381,10 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, cons
             const csd_head* hd = which ? target : draft;
             const HeadWs& ws = which ? wp : wq;
             HIP_TRY(head_body(hd, ws, t, R, st));
-            FinalArgs f = final_args(hd, ws, t, R);
+            TransArgs f = trans_args(hd, ws, t, R);
             f.seed = seed; f.row_offset = row_offset; f.tau = temperature;
             f.summary = summary; f.is_target = which;
-            HIP_TRY(launch_final(f, st));
+            HIP_TRY(launch_transition(f, st));
         }
     }
     const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
@@ -386,9 +409,9 @@ int csd_head_eval(const csd_head_t* head, const float* x, const float* z, int32_
     HIP_TRY(hipMemcpyAsync(ws.x, x, (size_t)n_rows * head->D * sizeof(float), hipMemcpyDeviceToDevice, st));
     HIP_TRY(cond_embed(head, z, ws, n_rows, st));
     HIP_TRY(head_body(head, ws, t, n_rows, st));
-    FinalArgs f = final_args(head, ws, t, n_rows);
+    TransArgs f = trans_args(head, ws, t, n_rows);
     f.raw_out = out; f.skip_coef = head->skip_sqrt[t];
-    HIP_TRY(launch_final(f, st));
+    HIP_TRY(launch_transition(f, st));
     return CSD_OK;
 }
 

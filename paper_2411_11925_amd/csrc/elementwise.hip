@@ -1,8 +1,7 @@
 // Row-wise kernels of the head and the sampler: conditioning SiLU, input
-// projection, layer-norm + modulation, and the fused "final" kernel that ends a
-// denoising step (final LN/modulation -> output projection -> Gaussian
-// transition of Eq. 3 with the shared noise eps_t -> log Sigma accumulation of
-// Eq. 6 / summary row at t = 1).
+// projection, layer-norm + modulation, and the transition kernel that ends a
+// denoising step (Gaussian transition of Eq. 3 with the shared noise eps_t,
+// log Sigma accumulation of Eq. 6, summary row at t = 1).
 #include "internal.hpp"
 #include "rng.hpp"
 
@@ -89,8 +88,11 @@ __device__ __forceinline__ void row_stats(const float* __restrict__ hrow, int W,
 }
 
 // ---------------------------------------------------------------- u = LN(h)*(1+scale)+shift
-template <typename TAct>
-__global__ void k_ln_mod(const float* __restrict__ h, const TAct* __restrict__ mod, int ldm, TAct* __restrict__ u,
+// OUT_SPLIT writes u as two bf16 halves [hi | lo] (lo = bf16(u - hi)) into a row of
+// 2W values, so that a bf16 GEMM against [w | w] sees u to ~2^-17 relative.
+enum { OUT_SAME = 0, OUT_SPLIT = 1 };
+template <typename TMod, typename TOut, int MODE>
+__global__ void k_ln_mod(const float* __restrict__ h, const TMod* __restrict__ mod, int ldm, TOut* __restrict__ u,
                          float ln_eps, int64_t R, int W) {
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -98,53 +100,46 @@ __global__ void k_ln_mod(const float* __restrict__ h, const TAct* __restrict__ m
     const float* hrow = h + r * W;
     float mean, rstd;
     row_stats(hrow, W, lane, ln_eps, mean, rstd);
-    const TAct* m = mod + r * (size_t)ldm;
+    const TMod* m = mod + r * (size_t)ldm;
     for (int j = lane; j < W; j += 64) {
         const float v = (hrow[j] - mean) * rstd;
-        act_store<TAct>(u, (size_t)r * W + j, fmaf(v, 1.0f + act_load<TAct>(m, W + j), act_load<TAct>(m, j)));
+        const float uv = fmaf(v, 1.0f + act_load<TMod>(m, W + j), act_load<TMod>(m, j));
+        if (MODE == OUT_SPLIT) {
+            const bf16_t hi = f32_to_bf16(uv);
+            ((bf16_t*)u)[(size_t)r * 2 * W + j] = hi;
+            ((bf16_t*)u)[(size_t)r * 2 * W + W + j] = f32_to_bf16(uv - bf16_to_f32(hi));
+        } else {
+            act_store<TOut>(u, (size_t)r * W + j, uv);
+        }
     }
 }
 
-hipError_t launch_ln_mod(const float* h, const void* mod, int ldm, void* u, int act, float ln_eps, int64_t R, int W, hipStream_t st) {
+hipError_t launch_ln_mod(const float* h, const void* mod, int ldm, int mod_is_f32, void* u, int out_mode,
+                         float ln_eps, int64_t R, int W, hipStream_t st) {
     if (R == 0) return hipSuccess;
     const int rows_per_block = 4;
     dim3 grid((unsigned)((R + rows_per_block - 1) / rows_per_block)), block(64 * rows_per_block);
-    if (act == ACT_BF16) hipLaunchKernelGGL(k_ln_mod<bf16_t>, grid, block, 0, st, h, (const bf16_t*)mod, ldm, (bf16_t*)u, ln_eps, R, W);
-    else hipLaunchKernelGGL(k_ln_mod<float>, grid, block, 0, st, h, (const float*)mod, ldm, (float*)u, ln_eps, R, W);
+    if (out_mode == LN_OUT_F32 && mod_is_f32)
+        hipLaunchKernelGGL((k_ln_mod<float, float, OUT_SAME>), grid, block, 0, st, h, (const float*)mod, ldm, (float*)u, ln_eps, R, W);
+    else if (out_mode == LN_OUT_BF16 && !mod_is_f32)
+        hipLaunchKernelGGL((k_ln_mod<bf16_t, bf16_t, OUT_SAME>), grid, block, 0, st, h, (const bf16_t*)mod, ldm, (bf16_t*)u, ln_eps, R, W);
+    else if (out_mode == LN_OUT_BF16_SPLIT && mod_is_f32)
+        hipLaunchKernelGGL((k_ln_mod<float, bf16_t, OUT_SPLIT>), grid, block, 0, st, h, (const float*)mod, ldm, (bf16_t*)u, ln_eps, R, W);
+    else
+        return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- end of a denoising step
-// One wave per row.  o = W_out (LN(h)*(1+scale)+shift) + b_out; lanes d < D then take
-// the reverse transition of coordinate d with eps_t regenerated from the counter RNG.
-template <typename TAct, int D>
-__global__ void k_final(FinalArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int64_t r = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (r >= a.R) return;
-    const int W = a.W;
-    const float* hrow = a.h + r * W;
-    float mean, rstd;
-    row_stats(hrow, W, lane, a.ln_eps, mean, rstd);
-    const TAct* m = (const TAct*)a.fmod + r * (size_t)a.ldm;
-    float acc[2 * D];
-#pragma unroll
-    for (int o = 0; o < 2 * D; ++o) acc[o] = 0.f;
-    for (int j = lane; j < W; j += 64) {
-        const float v = (hrow[j] - mean) * rstd;
-        const float u = fmaf(v, 1.0f + act_load<TAct>(m, W + j), act_load<TAct>(m, j));
-#pragma unroll
-        for (int o = 0; o < 2 * D; ++o) acc[o] = fmaf(u, a.w_out[(size_t)o * W + j], acc[o]);
-    }
-    float o_eps = 0.f, o_v = 0.f;    // lane d keeps o[d] and o[D+d]
-#pragma unroll
-    for (int o = 0; o < 2 * D; ++o) {
-        const float s = wave_sum(acc[o]) + a.b_out[o];
-        if (o == lane) o_eps = s;
-        if (o == lane + D) o_v = s;
-    }
-    if (lane >= D) return;
-    const int d = lane;
+// o = (eps_hat part, v part) of the output projection, [R, ldo] fp32.  The D lanes of a
+// row take the reverse transition of Eq. 3 with eps_t regenerated from the counter RNG.
+template <int D>
+__global__ void k_transition(TransArgs a) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t r = i / D;
+    const int d = (int)(i % D);
+    if (r >= a.R) return;                      // whole D-lane segments drop out together
+    const float o_eps = a.o[r * a.ldo + d], o_v = a.o[r * a.ldo + D + d];
     const float x = a.x[r * D + d];
     if (a.raw_out) {
         a.raw_out[r * 2 * D + d] = fmaf(a.skip_coef, x, o_eps);
@@ -156,7 +151,7 @@ __global__ void k_final(FinalArgs a) {
     const float eps = nrm[d & 3];
     const float lv = fmaf(o_v, a.coef.lhalf, a.coef.lmid);
     const float mu = fmaf(a.coef.cx, x, -a.coef.co * o_eps);
-    const float xn = fmaf(a.tau * __expf(0.5f * lv), eps, mu);
+    const float xn = fmaf(a.tau * expf(0.5f * lv), eps, mu);
     if (a.t >= 2) {
         a.x[r * D + d] = xn;
         float vs = o_v;                       // sum_d v_d over the D lanes of the row
@@ -173,19 +168,16 @@ __global__ void k_final(FinalArgs a) {
     }
 }
 
-hipError_t launch_final(const FinalArgs& a, hipStream_t st) {
+hipError_t launch_transition(const TransArgs& a, hipStream_t st) {
     if (a.R == 0) return hipSuccess;
-    const int rows_per_block = 4;
-    dim3 grid((unsigned)((a.R + rows_per_block - 1) / rows_per_block)), block(64 * rows_per_block);
-#define CSD_FINAL(TA, DD) hipLaunchKernelGGL((k_final<TA, DD>), grid, block, 0, st, a)
-    if (a.act == ACT_BF16) {
-        switch (a.D) { case 4: CSD_FINAL(bf16_t, 4); break; case 8: CSD_FINAL(bf16_t, 8); break;
-                       case 16: CSD_FINAL(bf16_t, 16); break; default: return hipErrorInvalidValue; }
-    } else {
-        switch (a.D) { case 4: CSD_FINAL(float, 4); break; case 8: CSD_FINAL(float, 8); break;
-                       case 16: CSD_FINAL(float, 16); break; default: return hipErrorInvalidValue; }
+    const int64_t n = a.R * a.D;
+    dim3 grid((unsigned)((n + 255) / 256)), block(256);
+    switch (a.D) {
+        case 4: hipLaunchKernelGGL(k_transition<4>, grid, block, 0, st, a); break;
+        case 8: hipLaunchKernelGGL(k_transition<8>, grid, block, 0, st, a); break;
+        case 16: hipLaunchKernelGGL(k_transition<16>, grid, block, 0, st, a); break;
+        default: return hipErrorInvalidValue;
     }
-#undef CSD_FINAL
     return hipGetLastError();
 }
 
@@ -269,6 +261,18 @@ hipError_t launch_f32_to_bf16(const float* src, bf16_t* dst, size_t n, hipStream
     if (n == 0) return hipSuccess;
     const size_t want = (n + 255) / 256;
     hipLaunchKernelGGL(k_f32_to_bf16, dim3((unsigned)(want < 8192 ? want : 8192)), dim3(256), 0, st, src, dst, n);
+    return hipGetLastError();
+}
+
+__global__ void k_f32_to_bf16_rows(const float* __restrict__ src, bf16_t* __restrict__ dst, int rows, int cols, int ld_dst) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < rows * cols) dst[(size_t)(i / cols) * ld_dst + i % cols] = f32_to_bf16(src[i]);
+}
+
+hipError_t launch_f32_to_bf16_rows(const float* src, bf16_t* dst, int rows, int cols, int ld_dst, hipStream_t st) {
+    const int n = rows * cols;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_f32_to_bf16_rows, dim3((n + 255) / 256), dim3(256), 0, st, src, dst, rows, cols, ld_dst);
     return hipGetLastError();
 }
 

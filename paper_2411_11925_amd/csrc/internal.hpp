@@ -53,6 +53,8 @@ struct csd_head {
     int D, C, W, L, T;
     float ln_eps;
     csd::Linear t1, t2, cond, in, fmod, out;
+    csd::Linear out_pad;                 // output layer padded to 64 rows; bf16 copy is [w | w] (2W per row)
+    float* d_out_pad = nullptr;          // storage of out_pad (fp32 w, b)
     std::vector<csd::Linear> mod, fc1, fc2;
     std::vector<csd::StepCoef> coef;     // [T+1], entry 0 unused
     std::vector<float> skip_sqrt;        // [T+1]: eps_skip_gain * sqrt(1 - abar_t)
@@ -91,14 +93,13 @@ hipError_t launch_cond_silu(const float* e, const float* time_emb_t, void* s, in
 // h = W_in x + b_in
 hipError_t launch_inproj(const float* x, const float* w, const float* b, float* h, int64_t R, int D, int W, hipStream_t st);
 // u = LN(h)*(1+scale)+shift with (shift,scale) = mod[:, 0:W], mod[:, W:2W]
-hipError_t launch_ln_mod(const float* h, const void* mod, int ldm, void* u, int act, float ln_eps, int64_t R, int W, hipStream_t st);
+enum { LN_OUT_F32 = 0, LN_OUT_BF16 = 1, LN_OUT_BF16_SPLIT = 2 };   // split: [hi | lo] bf16, 2W per row
+hipError_t launch_ln_mod(const float* h, const void* mod, int ldm, int mod_is_f32, void* u, int out_mode,
+                         float ln_eps, int64_t R, int W, hipStream_t st);
 
-struct FinalArgs {
-    const float* h; const void* fmod; int ldm; int act;   // final LN + modulation inputs
-    const float* w_out; const float* b_out;               // [2D, W], [2D]
-    float ln_eps;
-    int64_t R; int W; int D;
-    // transition
+struct TransArgs {
+    const float* o; int ldo;   // [R, ldo] fp32 output projection: columns [0,D) eps part, [D,2D) v
+    int64_t R; int D;
     float* x;                  // [R,D] in: x_t, out: x_{t-1} (not written at t = 1)
     float* acc;                // [R] running 1/2 sum_d (log sigma^2 - lmid_t), t >= 2
     StepCoef coef; int t;
@@ -107,7 +108,7 @@ struct FinalArgs {
     float* raw_out;            // optional [R,2D]: (eps_hat, v) for csd_head_eval; skips the transition
     float skip_coef;           // eps_skip_gain * sqrt(1 - abar_t), for raw_out only
 };
-hipError_t launch_final(const FinalArgs& a, hipStream_t st);
+hipError_t launch_transition(const TransArgs& a, hipStream_t st);
 
 hipError_t launch_init_x(float* xq, float* xp, float* accq, float* accp, int64_t R, int D, int T,
                          uint64_t seed, uint64_t row_offset, hipStream_t st);
@@ -124,5 +125,7 @@ hipError_t launch_rng_normals(uint64_t seed, uint64_t row_offset, int64_t R, int
 hipError_t launch_rng_uniforms(uint64_t seed, uint64_t row_offset, int64_t R, int slot, int stream_id,
                                float* out, hipStream_t st);
 hipError_t launch_f32_to_bf16(const float* src, bf16_t* dst, size_t n, hipStream_t st);
+// dst[r*ld_dst + c] = bf16(src[r*cols + c])
+hipError_t launch_f32_to_bf16_rows(const float* src, bf16_t* dst, int rows, int cols, int ld_dst, hipStream_t st);
 
 }  // namespace csd
