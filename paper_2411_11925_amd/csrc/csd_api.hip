@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdarg>
 #include <cstring>
+#include <cstdlib>
 #include <new>
 #include <string>
 
@@ -169,6 +170,26 @@ TransArgs trans_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
     f.o = ws.o; f.ldo = 64; f.R = R; f.D = hd->D; f.x = ws.x; f.acc = ws.acc;
     f.coef = hd->coef[t]; f.t = t;
     return f;
+}
+
+// side stream (default priority) and its fork/join events, one set per device, created on
+// first use and kept until the process ends.  CSD_SINGLE_STREAM=1 keeps everything on the
+// caller's stream.
+struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; bool ok = false; };
+
+SideStream* side_stream(int device) {
+    static SideStream streams[16];
+    static int disabled = -1;
+    if (disabled < 0) { const char* e = getenv("CSD_SINGLE_STREAM"); disabled = (e && *e == '1') ? 1 : 0; }
+    if (disabled || device < 0 || device >= 16) return nullptr;
+    SideStream& s = streams[device];
+    if (!s.ok) {
+        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+        s.ok = true;
+    }
+    return &s;
 }
 
 struct DeviceGuard {
@@ -373,19 +394,36 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, cons
     char* p = carve(draft, R, (char*)workspace, &wq);
     carve(target, R, p, &wp);
 
+    // The two heads never exchange data inside the T steps (they only share the noise,
+    // which each regenerates from the counters), so the draft chain runs on a side
+    // stream next to the target chain: one chain's memory-bound kernels and epilogues
+    // fill the gaps of the other's MFMA loops.  Fork and join are events on the caller's
+    // stream; the call still does not synchronise the host.
     HIP_TRY(launch_init_x(wq.x, wp.x, wq.acc, wp.acc, R, D, T, seed, row_offset, st));
-    HIP_TRY(cond_embed(draft, z_q, wq, R, st));
+    SideStream* side = side_stream(draft->device);
+    hipStream_t sq = st;
+    if (side) {
+        HIP_TRY(hipEventRecord(side->fork, st));
+        HIP_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
+        sq = side->stream;
+    }
+    HIP_TRY(cond_embed(draft, z_q, wq, R, sq));
     HIP_TRY(cond_embed(target, z_p, wp, R, st));
     for (int t = T; t >= 1; --t) {
         for (int which = 0; which < 2; ++which) {
             const csd_head* hd = which ? target : draft;
             const HeadWs& ws = which ? wp : wq;
-            HIP_TRY(head_body(hd, ws, t, R, st));
+            hipStream_t s = which ? st : sq;
+            HIP_TRY(head_body(hd, ws, t, R, s));
             TransArgs f = trans_args(hd, ws, t, R);
             f.seed = seed; f.row_offset = row_offset; f.tau = temperature;
             f.summary = summary; f.is_target = which;
-            HIP_TRY(launch_transition(f, st));
+            HIP_TRY(launch_transition(f, s));
         }
+    }
+    if (side) {
+        HIP_TRY(hipEventRecord(side->join, side->stream));
+        HIP_TRY(hipStreamWaitEvent(st, side->join, 0));
     }
     const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
     HIP_TRY(launch_finish_summary(summary, wq.acc, wp.acc, ref_diff, R, D, st));

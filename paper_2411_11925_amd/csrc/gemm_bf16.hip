@@ -54,6 +54,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     constexpr int GROUPS = (BM + BN) / 8;              // 8-row groups (1 KiB of LDS) per stage
     constexpr int GPW = GROUPS / NW;                   // groups loaded by each wave
     static_assert(GROUPS % NW == 0 && NW % 2 == 0 && (BM / 8) % 2 == 0, "loader mapping");
+    static_assert(NW * 32 * TN * 4 <= 2 * (BM + BN) * ROW_B, "epilogue staging must fit in the LDS of the main loop");
     constexpr int STAGE_B = (BM + BN) * ROW_B;
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
@@ -137,35 +138,50 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
         __syncthreads();
     }
 
-    // ---- epilogue: lane holds, per block (i,j) and q, features n..n+3 of row m
+    // ---- epilogue.  After the MFMAs a lane holds, per 32x32 block (i,j) and q, 4
+    // consecutive features of ONE row, i.e. a wave store would touch 32 rows with 16
+    // bytes each.  Each wave therefore transposes one 32-row slab at a time through a
+    // private piece of the (now idle) LDS and walks it row-wise: NCH lanes cover the
+    // TN*4 contiguous bytes of a row, so global loads and stores use whole cache lines.
+    constexpr int NCH = TN / 4;                              // 16-byte chunks per staged row
+    constexpr int RPP = 64 / NCH;                            // rows per pass of the wave
+    float* stg = reinterpret_cast<float*>(smem + wave * (32 * TN * 4));
+    auto stg_swz = [](int row) { return NCH >= 16 ? (row & 15) : ((row >> 1) & (NCH - 1)); };
+    const int rd_row0 = lane / NCH, rd_c = lane % NCH;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
-        const int64_t m = m0 + wm * TM + i * 32 + l32;
-        if (m >= p.M) continue;
 #pragma unroll
-        for (int j = 0; j < FN; ++j) {
+        for (int j = 0; j < FN; ++j)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * TN + j * 32 + q * 8 + khalf * 4;
-                const float4 bb = *reinterpret_cast<const float4*>(p.bias + n);
-                float v0 = acc[i][j][4 * q + 0] + bb.x, v1 = acc[i][j][4 * q + 1] + bb.y;
-                float v2 = acc[i][j][4 * q + 2] + bb.z, v3 = acc[i][j][4 * q + 3] + bb.w;
-                if (EPI == EPI_BIAS_SILU) { v0 = silu_fast(v0); v1 = silu_fast(v1); v2 = silu_fast(v2); v3 = silu_fast(v3); }
-                if (EPI == EPI_GATE_RES) {
-                    const uint2 g = *reinterpret_cast<const uint2*>(p.gate + m * p.ldg + n);
-                    float* cp = (float*)p.C + m * p.ldc + n;
-                    const float4 c = *reinterpret_cast<const float4*>(cp);
-                    v0 = fmaf(bf16_to_f32((bf16_t)(g.x & 0xFFFF)), v0, c.x);
-                    v1 = fmaf(bf16_to_f32((bf16_t)(g.x >> 16)), v1, c.y);
-                    v2 = fmaf(bf16_to_f32((bf16_t)(g.y & 0xFFFF)), v2, c.z);
-                    v3 = fmaf(bf16_to_f32((bf16_t)(g.y >> 16)), v3, c.w);
-                    *reinterpret_cast<float4*>(cp) = make_float4(v0, v1, v2, v3);
-                } else if (OUT_F32) {
-                    *reinterpret_cast<float4*>((float*)p.C + m * p.ldc + n) = make_float4(v0, v1, v2, v3);
-                } else {
-                    *reinterpret_cast<uint2*>((bf16_t*)p.C + m * p.ldc + n) =
-                        make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
-                }
+                const int c = j * 8 + q * 2 + khalf;
+                *reinterpret_cast<float4*>(stg + l32 * TN + ((c ^ stg_swz(l32)) << 2)) =
+                    make_float4(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+            }
+        const int n = n0 + wn * TN + rd_c * 4;
+        const float4 bb = *reinterpret_cast<const float4*>(p.bias + n);
+#pragma unroll
+        for (int pass = 0; pass < 32 / RPP; ++pass) {
+            const int row = pass * RPP + rd_row0;
+            const float4 a4 = *reinterpret_cast<const float4*>(stg + row * TN + ((rd_c ^ stg_swz(row)) << 2));
+            const int64_t m = m0 + wm * TM + i * 32 + row;
+            if (m >= p.M) continue;
+            float v0 = a4.x + bb.x, v1 = a4.y + bb.y, v2 = a4.z + bb.z, v3 = a4.w + bb.w;
+            if (EPI == EPI_BIAS_SILU) { v0 = silu_fast(v0); v1 = silu_fast(v1); v2 = silu_fast(v2); v3 = silu_fast(v3); }
+            if (EPI == EPI_GATE_RES) {
+                const uint2 g = *reinterpret_cast<const uint2*>(p.gate + m * p.ldg + n);
+                float* cp = (float*)p.C + m * p.ldc + n;
+                const float4 c = *reinterpret_cast<const float4*>(cp);
+                v0 = fmaf(bf16_to_f32((bf16_t)(g.x & 0xFFFF)), v0, c.x);
+                v1 = fmaf(bf16_to_f32((bf16_t)(g.x >> 16)), v1, c.y);
+                v2 = fmaf(bf16_to_f32((bf16_t)(g.y & 0xFFFF)), v2, c.z);
+                v3 = fmaf(bf16_to_f32((bf16_t)(g.y >> 16)), v3, c.w);
+                *reinterpret_cast<float4*>(cp) = make_float4(v0, v1, v2, v3);
+            } else if (OUT_F32) {
+                *reinterpret_cast<float4*>((float*)p.C + m * p.ldc + n) = make_float4(v0, v1, v2, v3);
+            } else {
+                *reinterpret_cast<uint2*>((bf16_t*)p.C + m * p.ldc + n) =
+                    make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
             }
         }
     }
