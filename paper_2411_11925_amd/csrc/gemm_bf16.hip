@@ -31,9 +31,6 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int BK = 64;
-constexpr int ROW_B = BK * 2;           // bytes per LDS row
-
 __device__ __forceinline__ float silu_fast(float a) { return a / (1.0f + __expf(-a)); }
 
 struct Params {
@@ -46,16 +43,26 @@ struct Params {
     int tiles_m, tiles_n;
 };
 
-template <int BM, int BN, int WM, int WN, int EPI, bool OUT_F32>
+// s_waitcnt with only vmcnt set (expcnt and lgkmcnt left at "don't wait")
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI, bool OUT_F32>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;          // per-wave tile
     constexpr int FM = TM / 32, FN = TN / 32;          // 32x32 blocks per wave
-    constexpr int GROUPS = (BM + BN) / 8;              // 8-row groups (1 KiB of LDS) per stage
-    constexpr int GPW = GROUPS / NW;                   // groups loaded by each wave
-    static_assert(GROUPS % NW == 0 && NW % 2 == 0 && (BM / 8) % 2 == 0, "loader mapping");
-    static_assert(NW * 32 * TN * 4 <= 2 * (BM + BN) * ROW_B, "epilogue staging must fit in the LDS of the main loop");
+    constexpr int ROW_B = BK * 2;                      // bytes per LDS row
+    constexpr int CPR = BK / 8;                        // 16-byte chunks per row (8 or 4)
+    constexpr int RPL = 64 / CPR;                      // rows written by one wave-wide direct load
+    constexpr int SH = (CPR == 8) ? 1 : 2;             // log2(rows per 256-byte bank window)
+    constexpr int GROUPS = (BM + BN) / RPL;            // direct loads (1 KiB of LDS each) per slab
+    constexpr int GPW = GROUPS / NW;                   // ... issued by each wave
+    static_assert(BK == 64 || BK == 32, "BK");
+    static_assert(GROUPS % NW == 0 && NW % 2 == 0 && (BM / RPL) % 2 == 0, "loader mapping");
     constexpr int STAGE_B = (BM + BN) * ROW_B;
+    static_assert(NW * 32 * TN * 4 <= NST * STAGE_B, "epilogue staging must fit in the LDS of the main loop");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // ---- tile of this workgroup: ids sharing id%8 (one XCD) sweep n first, then m
@@ -73,16 +80,18 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     const int wm = wave / WN, wn = wave % WN;
     const int l32 = lane & 31, khalf = lane >> 5;
 
-    // ---- loader: lane (lr, pc) of a group writes LDS row lr, physical chunk pc
-    const int lr = lane >> 3, pc = lane & 7;
-    const int ld_chunk = pc ^ ((((wave & 1) << 2) + (lr >> 1)) & 7);   // logical chunk to fetch
+    // ---- loader: lane (lr, pc) of a direct load writes LDS row lr, physical chunk pc, and
+    // fetches the logical chunk pc ^ swizzle(row) that belongs there
+    const int lr = lane / CPR, pc = lane % CPR;
+    const int ld_swz = (CPR == 8) ? ((((wave & 1) << 2) + (lr >> 1)) & 7) : ((lr >> 2) & 3);
+    const int ld_chunk = pc ^ ld_swz;
     auto issue_loads = [&](int stage, int k0) {
 #pragma unroll
         for (int i = 0; i < GPW; ++i) {
-            const int g = wave + i * NW;               // group index: rows 8g .. 8g+7 of the stage
-            const int row = g * 8 + lr;
+            const int g = wave + i * NW;               // rows RPL*g .. RPL*g+RPL-1 of the slab
+            const int row = g * RPL + lr;
             const bf16_t* src;
-            if (g < BM / 8) {                          // uniform per wave and i
+            if (g < BM / RPL) {                        // uniform per wave and i
                 int64_t r = m0 + row;
                 r = r < p.M ? r : (int64_t)p.M - 1;
                 src = p.A + r * p.lda + k0 + ld_chunk * 8;
@@ -94,8 +103,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
         }
     };
 
-    // ---- fragment read offsets (bytes) of this lane for the 4 k16-steps of a slab
-    const int swz = (l32 >> 1) & 7;
+    // ---- fragment read offsets (bytes) of this lane for the k16-steps of a slab
+    const int swz = (l32 >> SH) & (CPR - 1);
     int koff[BK / 16];
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) koff[kk] = ((kk * 2 + khalf) ^ swz) * 16;
@@ -110,15 +119,19 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // ---- main loop: NST-deep ring of slabs.  At step kt the slabs kt .. kt+NST-2 are in
+    // flight; wait for slab kt only, barrier (which also says everyone is done reading
+    // slab kt-1), refill the stage of slab kt-1 with slab kt+NST-1, then compute slab kt.
     const int nk = p.K / BK;
-    issue_loads(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): this wave's direct loads have landed
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NST - 1; ++s)
+        if (s < nk) issue_loads(s, s * BK);
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) issue_loads(cur ^ 1, (kt + 1) * BK);
-        const unsigned char* sa = smem + cur * STAGE_B + a_row_off;
-        const unsigned char* sb = smem + cur * STAGE_B + b_row_off;
+        if (kt + NST - 2 < nk) wait_vmcnt<GPW * (NST - 2)>(); else wait_vmcnt<0>();
+        __syncthreads();
+        if (kt + NST - 1 < nk) issue_loads((kt + NST - 1) % NST, (kt + NST - 1) * BK);
+        const unsigned char* sa = smem + (kt % NST) * STAGE_B + a_row_off;
+        const unsigned char* sb = smem + (kt % NST) * STAGE_B + b_row_off;
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 fa[FM], fb[FN];
@@ -134,9 +147,8 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
                 for (int j = 0; j < FN; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
     }
+    __syncthreads();      // all waves are done with the last slab: LDS is free for the epilogue
 
     // ---- epilogue.  After the MFMAs a lane holds, per 32x32 block (i,j) and q, 4
     // consecutive features of ONE row, i.e. a wave store would touch 32 rows with 16
@@ -187,18 +199,18 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int BK, int NST>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     Params p;
     p.A = (const bf16_t*)g.A; p.lda = g.lda; p.B = (const bf16_t*)g.B; p.bias = g.bias;
     p.C = g.C; p.ldc = g.ldc; p.gate = (const bf16_t*)g.gate; p.ldg = g.ldg;
     p.M = g.M; p.N = g.N; p.K = g.K;
     p.tiles_m = (g.M + BM - 1) / BM; p.tiles_n = g.N / BN;
-    const size_t smem = (size_t)2 * (BM + BN) * ROW_B;
+    const size_t smem = (size_t)NST * (BM + BN) * BK * 2;
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WM * WN * 64);
 #define CSD_LAUNCH(EPI, F32)                                                                                   \
     do {                                                                                                       \
-        auto kern = k_gemm_bf16<BM, BN, WM, WN, EPI, F32>;                                                      \
+        auto kern = k_gemm_bf16<BM, BN, WM, WN, BK, NST, EPI, F32>;                                             \
         static bool attr_done = false;                                                                          \
         if (!attr_done) {                                                                                       \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
@@ -228,18 +240,21 @@ int gemm_variant_override() {
 
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
     if (g.M == 0) return hipSuccess;
-    if (g.K % BK != 0 || g.N % 64 != 0 || g.lda % 8 != 0 || g.ldc % 4 != 0) return hipErrorInvalidValue;
+    if (g.K % 64 != 0 || g.N % 64 != 0 || g.lda % 8 != 0 || g.ldc % 4 != 0) return hipErrorInvalidValue;
     if (((uintptr_t)g.A & 15u) || ((uintptr_t)g.B & 15u) || ((uintptr_t)g.C & 15u)) return hipErrorInvalidValue;
     if (g.epi == EPI_GATE_RES && (g.ldg % 4 != 0 || ((uintptr_t)g.gate & 7u))) return hipErrorInvalidValue;
     int variant = gemm_variant_override();
     if (variant < 0) variant = (g.N % 256 == 0 && g.M >= 2048) ? 1 : (g.N % 128 == 0 && g.M >= 256) ? 2 : 3;
     if ((variant == 0 || variant == 1) && g.N % 256 != 0) variant = 3;
-    if (variant == 2 && g.N % 128 != 0) variant = 3;
+    if ((variant == 2 || variant >= 4) && g.N % 128 != 0) variant = 3;
     switch (variant) {
-        case 0: return launch_cfg<256, 256, 2, 2>(g, st);    // 4 waves, 128x128 per wave
-        case 1: return launch_cfg<256, 256, 2, 4>(g, st);    // 8 waves, 128x64 per wave
-        case 2: return launch_cfg<128, 128, 2, 2>(g, st);    // 4 waves, 64x64 per wave
-        default: return launch_cfg<64, 64, 2, 2>(g, st);     // 4 waves, 32x32 per wave
+        case 0: return launch_cfg<256, 256, 2, 2, 64, 2>(g, st);    // 4 waves, 128x128 per wave, 128 KiB LDS
+        case 1: return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);    // 8 waves, 128x64 per wave, 128 KiB LDS
+        case 2: return launch_cfg<128, 128, 2, 2, 64, 2>(g, st);    // 4 waves, 64x64 per wave, 64 KiB LDS
+        case 4: return launch_cfg<256, 128, 2, 2, 32, 3>(g, st);    // 4 waves, 128x64 per wave, 72 KiB LDS: 2 per CU
+        case 5: return launch_cfg<256, 128, 2, 2, 32, 2>(g, st);    // same, 48 KiB LDS
+        case 6: return launch_cfg<256, 128, 2, 2, 64, 2>(g, st);    // same tile, BK 64, 96 KiB LDS
+        default: return launch_cfg<64, 64, 2, 2, 64, 2>(g, st);     // 4 waves, 32x32 per wave
     }
 }
 
