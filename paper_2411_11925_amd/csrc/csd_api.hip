@@ -55,7 +55,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // device buffers of one head for R rows, carved from the caller's workspace
 struct HeadWs {
-    float* e; void* s; void* mod; float* fm; float* h; void* u; void* a; float* o; float* x; float* acc;
+    float* e; void* s; void* mod[2]; float* fm; float* h; void* u; void* a; void* y; float* o; float* x; float* acc;
 };
 
 size_t head_ws_bytes(const csd_head* hd, int64_t R) {
@@ -63,11 +63,11 @@ size_t head_ws_bytes(const csd_head* hd, int64_t R) {
     size_t n = 0;
     n += align_up(r * W * 4, 256);          // e
     n += align_up(r * W * act, 256);        // s
-    n += align_up(r * 3 * W * act, 256);    // mod (one block at a time)
+    n += 2 * align_up(r * 3 * W * act, 256);  // mod of the current and the previous block
     n += align_up(r * 2 * W * 4, 256);      // fm (fp32 in both modes)
     n += align_up(r * W * 4, 256);          // h
     n += align_up(r * W * 4, 256);          // u (fp32, bf16, or the [hi|lo] bf16 pair of the last layer)
-    n += align_up(r * W * act, 256);        // a
+    n += 2 * align_up(r * W * act, 256);    // a, y
     n += align_up(r * 64 * 4, 256);         // o (output projection, padded to 64 columns)
     n += align_up(r * hd->D * 4, 256);      // x
     n += align_up(r * 4, 256);              // acc
@@ -79,11 +79,13 @@ char* carve(const csd_head* hd, int64_t R, char* p, HeadWs* ws) {
     auto take = [&](size_t bytes) { char* q = p; p += align_up(bytes, 256); return q; };
     ws->e = (float*)take(r * W * 4);
     ws->s = take(r * W * act);
-    ws->mod = take(r * 3 * W * act);
+    ws->mod[0] = take(r * 3 * W * act);
+    ws->mod[1] = take(r * 3 * W * act);
     ws->fm = (float*)take(r * 2 * W * 4);
     ws->h = (float*)take(r * W * 4);
     ws->u = take(r * W * 4);
     ws->a = take(r * W * act);
+    ws->y = take(r * W * act);
     ws->o = (float*)take(r * 64 * 4);
     ws->x = (float*)take(r * hd->D * 4);
     ws->acc = (float*)take(r * 4);
@@ -122,42 +124,41 @@ hipError_t cond_embed(const csd_head* hd, const float* z, const HeadWs& ws, int6
     return launch_gemm_f32(g, st);
 }
 
-// everything of step t up to (not including) the final kernel: leaves h and fm ready
+// everything of step t up to (not including) the transition kernel: leaves o ready
 hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hipStream_t st) {
-    const int W = hd->W;
+    const int W = hd->W, L = hd->L;
     const bool b16 = hd->cfg.gemm_dtype == CSD_BF16;
     const int act = b16 ? ACT_BF16 : ACT_F32;
     const size_t asz = b16 ? 2 : 4;
     hipError_t e;
     if ((e = launch_cond_silu(ws.e, hd->d_time_emb + (size_t)t * W, ws.s, act, R, W, st)) != hipSuccess) return e;
-    if ((e = launch_inproj(ws.x, hd->in.w, hd->in.b, ws.h, R, hd->D, W, st)) != hipSuccess) return e;
-    for (int l = 0; l < hd->L; ++l) {
+    BlockPreArgs bp{};
+    bp.act = act; bp.h = ws.h; bp.y = ws.y; bp.u = ws.u; bp.ln_eps = hd->ln_eps; bp.R = R; bp.W = W; bp.D = hd->D;
+    bp.x = ws.x; bp.w_in = hd->in.w; bp.b_in = hd->in.b;
+    for (int l = 0; l <= L; ++l) {
+        // modulation of block l (l = L: the final one, kept in fp32 because it feeds eps_hat directly)
+        void* mod = (l == L) ? (void*)ws.fm : ws.mod[l & 1];
+        const Linear& ml = (l == L) ? hd->fmod : hd->mod[l];
         GemmArgs g{};
-        g.M = (int)R; g.K = W;
-        // (shift, scale, gate) = Lin_mod(s)
-        g.A = ws.s; g.lda = W; g.B = b16 ? (const void*)hd->mod[l].w16 : (const void*)hd->mod[l].w;
-        g.bias = hd->mod[l].b; g.C = ws.mod; g.ldc = 3 * W; g.N = 3 * W; g.epi = EPI_BIAS;
-        if ((e = gemm_timed(hd, g, st)) != hipSuccess) return e;
-        if ((e = launch_ln_mod(ws.h, ws.mod, 3 * W, b16 ? 0 : 1, ws.u, b16 ? LN_OUT_BF16 : LN_OUT_F32, hd->ln_eps, R, W, st)) != hipSuccess) return e;
-        // a = silu(fc1 u)
+        g.M = (int)R; g.K = W; g.A = ws.s; g.lda = W;
+        g.B = b16 ? (const void*)ml.w16 : (const void*)ml.w; g.bias = ml.b;
+        g.C = mod; g.N = ml.n_out; g.ldc = ml.n_out; g.epi = EPI_BIAS; g.c_is_f32 = (l == L) ? 1 : 0;
+        if ((e = (l == L) ? gemm(hd, g, st) : gemm_timed(hd, g, st)) != hipSuccess) return e;
+        // residual of block l-1 (or the input projection), LN, modulation -> u
+        bp.mode = (l == 0) ? 0 : (l == L ? 2 : 1);
+        bp.mod = mod; bp.ldm = ml.n_out;
+        if (l > 0) { bp.gate = (const char*)ws.mod[(l - 1) & 1] + (size_t)2 * W * asz; bp.ldg = 3 * W; }
+        if ((e = launch_block_pre(bp, st)) != hipSuccess) return e;
+        if (l == L) break;
+        // a = silu(fc1 u);  y = fc2 a
         g.A = ws.u; g.B = b16 ? (const void*)hd->fc1[l].w16 : (const void*)hd->fc1[l].w;
-        g.bias = hd->fc1[l].b; g.C = ws.a; g.ldc = W; g.N = W; g.epi = EPI_BIAS_SILU;
+        g.bias = hd->fc1[l].b; g.C = ws.a; g.ldc = W; g.N = W; g.epi = EPI_BIAS_SILU; g.c_is_f32 = 0;
         if ((e = gemm(hd, g, st)) != hipSuccess) return e;
-        // h += gate * fc2 a
         g.A = ws.a; g.B = b16 ? (const void*)hd->fc2[l].w16 : (const void*)hd->fc2[l].w;
-        g.bias = hd->fc2[l].b; g.C = ws.h; g.ldc = W; g.N = W; g.epi = EPI_GATE_RES;
-        g.gate = (const char*)ws.mod + (size_t)2 * W * asz; g.ldg = 3 * W;
+        g.bias = hd->fc2[l].b; g.C = ws.y; g.epi = EPI_BIAS;
         if ((e = gemm(hd, g, st)) != hipSuccess) return e;
     }
-    GemmArgs g{};
-    g.M = (int)R; g.K = W; g.A = ws.s; g.lda = W;
-    g.B = b16 ? (const void*)hd->fmod.w16 : (const void*)hd->fmod.w; g.bias = hd->fmod.b;
-    g.C = ws.fm; g.ldc = 2 * W; g.N = 2 * W; g.epi = EPI_BIAS;
-    g.c_is_f32 = 1;     // the last modulation feeds eps_hat directly: kept in fp32
-    if ((e = gemm(hd, g, st)) != hipSuccess) return e;
-    // o = Lin_out(LN(h)*(1+scale)+shift), padded to 64 columns.  In bf16 mode the input goes
-    // in as a [hi | lo] bf16 pair against [w | w], i.e. with fp32-like accuracy.
-    if ((e = launch_ln_mod(ws.h, ws.fm, 2 * W, 1, ws.u, b16 ? LN_OUT_BF16_SPLIT : LN_OUT_F32, hd->ln_eps, R, W, st)) != hipSuccess) return e;
+    // o = Lin_out(u), padded to 64 columns.  In bf16 mode u is the [hi | lo] pair against [w | w].
     GemmArgs go{};
     go.M = (int)R; go.N = 64; go.K = b16 ? 2 * W : W; go.A = ws.u; go.lda = go.K;
     go.B = b16 ? (const void*)hd->out_pad.w16 : (const void*)hd->out_pad.w; go.bias = hd->out_pad.b;

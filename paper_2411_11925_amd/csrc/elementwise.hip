@@ -1,6 +1,6 @@
-// Row-wise kernels of the head and the sampler: conditioning SiLU, input
-// projection, layer-norm + modulation, and the transition kernel that ends a
-// denoising step (Gaussian transition of Eq. 3 with the shared noise eps_t,
+// Row-wise kernels of the head and the sampler: conditioning SiLU, the fused start of a
+// block (input projection or residual, layer-norm, modulation), and the transition kernel
+// that ends a denoising step (Gaussian transition of Eq. 3 with the shared noise eps_t,
 // log Sigma accumulation of Eq. 6, summary row at t = 1).
 #include "internal.hpp"
 #include "rng.hpp"
@@ -45,89 +45,160 @@ hipError_t launch_cond_silu(const float* e, const float* temb, void* s, int act,
     return hipGetLastError();
 }
 
-// ---------------------------------------------------------------- h = W_in x + b_in
-// one thread per (row, output feature); D <= 16 inputs
-template <int D>
-__global__ void k_inproj(const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ b,
-                         float* __restrict__ h, int64_t R, int W) {
-    const int64_t r = blockIdx.y;
-    const int o = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= R || o >= W) return;
-    float acc = b[o];
-#pragma unroll
-    for (int d = 0; d < D; ++d) acc = fmaf(w[(size_t)o * D + d], x[r * D + d], acc);
-    h[r * W + o] = acc;
+// ---------------------------------------------------------------- start of a block
+// One wave per row, the row held in registers, one pass over memory:
+//   FIRST : h = W_in x + b_in                      (input projection of the head)
+//   MIDDLE: h += gate_prev * y_prev                (residual of the previous block)
+//   FINAL : same, then the last modulation comes in fp32
+// then LN statistics (two-pass, in registers) and u = LN(h)*(1+scale)+shift.
+// Writes h (fp32) and u.  With TAct = bf16 the FINAL u is written as a [hi | lo] bf16
+// pair (lo = bf16(u - hi)), 2W per row, so that a bf16 GEMM against [w | w] sees u to
+// ~2^-17 relative.
+enum { PRE_FIRST = 0, PRE_MIDDLE = 1, PRE_FINAL = 2 };
+
+template <typename T> __device__ __forceinline__ void load4(const T* p, float v[4]);
+template <> __device__ __forceinline__ void load4<float>(const float* p, float v[4]) {
+    const float4 t = *reinterpret_cast<const float4*>(p); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t* p, float v[4]) {
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xFFFF0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xFFFF0000u);
+}
+template <typename T> __device__ __forceinline__ void store4(T* p, const float v[4]);
+template <> __device__ __forceinline__ void store4<float>(float* p, const float v[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const float v[4]) {
+    *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
 }
 
-hipError_t launch_inproj(const float* x, const float* w, const float* b, float* h, int64_t R, int D, int W, hipStream_t st) {
-    if (R == 0) return hipSuccess;
-    // gridDim.y is limited to 65535: walk the rows in slabs
-    for (int64_t r0 = 0; r0 < R; r0 += 65535) {
-        const int64_t n = (R - r0 < 65535) ? R - r0 : 65535;
-        dim3 grid((W + 255) / 256, (unsigned)n), block(256);
-        const float* xs = x + r0 * D; float* hs = h + r0 * W;
-        switch (D) {
-            case 4: hipLaunchKernelGGL(k_inproj<4>, grid, block, 0, st, xs, w, b, hs, n, W); break;
-            case 8: hipLaunchKernelGGL(k_inproj<8>, grid, block, 0, st, xs, w, b, hs, n, W); break;
-            case 16: hipLaunchKernelGGL(k_inproj<16>, grid, block, 0, st, xs, w, b, hs, n, W); break;
-            default: return hipErrorInvalidValue;
-        }
-    }
-    return hipGetLastError();
-}
-
-// ---------------------------------------------------------------- LN statistics of one row by one wave
-__device__ __forceinline__ void row_stats(const float* __restrict__ hrow, int W, int lane, float ln_eps,
-                                          float& mean, float& rstd) {
-    float s = 0.f;
-    for (int j = lane; j < W; j += 64) s += hrow[j];
-    mean = wave_sum(s) / (float)W;
-    float q = 0.f;
-    for (int j = lane; j < W; j += 64) { const float d = hrow[j] - mean; q = fmaf(d, d, q); }
-    rstd = 1.0f / sqrtf(wave_sum(q) / (float)W + ln_eps);
-}
-
-// ---------------------------------------------------------------- u = LN(h)*(1+scale)+shift
-// OUT_SPLIT writes u as two bf16 halves [hi | lo] (lo = bf16(u - hi)) into a row of
-// 2W values, so that a bf16 GEMM against [w | w] sees u to ~2^-17 relative.
-enum { OUT_SAME = 0, OUT_SPLIT = 1 };
-template <typename TMod, typename TOut, int MODE>
-__global__ void k_ln_mod(const float* __restrict__ h, const TMod* __restrict__ mod, int ldm, TOut* __restrict__ u,
-                         float ln_eps, int64_t R, int W) {
+// NCH = W / 256 chunks of 4 consecutive features per lane (fast path); NCH = 0: any W % 64 == 0,
+// one feature per lane and step, three passes (the row is re-read from cache instead of registers).
+template <typename TAct, int MODE, int D, int NCH>
+__global__ __launch_bounds__(256) void k_block_pre(BlockPreArgs a) {
     const int lane = threadIdx.x & 63;
     const int64_t r = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    if (r >= R) return;
-    const float* hrow = h + r * W;
-    float mean, rstd;
-    row_stats(hrow, W, lane, ln_eps, mean, rstd);
-    const TMod* m = mod + r * (size_t)ldm;
-    for (int j = lane; j < W; j += 64) {
-        const float v = (hrow[j] - mean) * rstd;
-        const float uv = fmaf(v, 1.0f + act_load<TMod>(m, W + j), act_load<TMod>(m, j));
-        if (MODE == OUT_SPLIT) {
-            const bf16_t hi = f32_to_bf16(uv);
-            ((bf16_t*)u)[(size_t)r * 2 * W + j] = hi;
-            ((bf16_t*)u)[(size_t)r * 2 * W + W + j] = f32_to_bf16(uv - bf16_to_f32(hi));
+    if (r >= a.R) return;
+    const int W = a.W;
+    float* hrow = a.h + r * W;
+    const TAct* yrow = (const TAct*)a.y + r * (size_t)W;
+    const TAct* grow = (const TAct*)a.gate + r * (size_t)a.ldg;
+    float xr[D];
+    if (MODE == PRE_FIRST) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) xr[d] = a.x[r * D + d];
+    }
+    auto h_at = [&](int j, float out[4], int n) {        // n consecutive features from j
+        if (MODE == PRE_FIRST) {
+            for (int e = 0; e < n; ++e) {
+                float acc = a.b_in[j + e];
+#pragma unroll
+                for (int d = 0; d < D; ++d) acc = fmaf(a.w_in[(size_t)(j + e) * D + d], xr[d], acc);
+                out[e] = acc;
+            }
+        } else if (n == 4) {
+            float hv[4], yv[4], gv[4];
+            load4<float>(hrow + j, hv); load4<TAct>(yrow + j, yv); load4<TAct>(grow + j, gv);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) out[e] = fmaf(gv[e], yv[e], hv[e]);
         } else {
-            act_store<TOut>(u, (size_t)r * W + j, uv);
+            out[0] = fmaf(act_load<TAct>(grow, j), act_load<TAct>(yrow, j), hrow[j]);
         }
+    };
+    auto emit = [&](int j, const float hv[4], int n, float mean, float rstd) {
+        float sh[4], sc[4], uv[4];
+        if (n == 4) {
+            if (MODE == PRE_FINAL) { load4<float>((const float*)a.mod + r * (size_t)a.ldm + j, sh); load4<float>((const float*)a.mod + r * (size_t)a.ldm + W + j, sc); }
+            else { load4<TAct>((const TAct*)a.mod + r * (size_t)a.ldm + j, sh); load4<TAct>((const TAct*)a.mod + r * (size_t)a.ldm + W + j, sc); }
+        } else {
+            if (MODE == PRE_FINAL) { sh[0] = ((const float*)a.mod)[r * (size_t)a.ldm + j]; sc[0] = ((const float*)a.mod)[r * (size_t)a.ldm + W + j]; }
+            else { sh[0] = act_load<TAct>((const TAct*)a.mod + r * (size_t)a.ldm, j); sc[0] = act_load<TAct>((const TAct*)a.mod + r * (size_t)a.ldm, W + j); }
+        }
+        for (int e = 0; e < n; ++e) uv[e] = fmaf((hv[e] - mean) * rstd, 1.0f + sc[e], sh[e]);
+        if (MODE == PRE_FINAL && sizeof(TAct) == 2) {        // [hi | lo] split
+            bf16_t* urow = (bf16_t*)a.u + r * (size_t)2 * W;
+            float lo[4];
+            for (int e = 0; e < n; ++e) lo[e] = uv[e] - bf16_to_f32(f32_to_bf16(uv[e]));
+            if (n == 4) { store4<bf16_t>(urow + j, uv); store4<bf16_t>(urow + W + j, lo); }
+            else { urow[j] = f32_to_bf16(uv[0]); urow[W + j] = f32_to_bf16(lo[0]); }
+        } else {
+            TAct* urow = (TAct*)a.u + r * (size_t)W;
+            if (n == 4) store4<TAct>(urow + j, uv); else act_store<TAct>(urow, j, uv[0]);
+        }
+    };
+    if (NCH > 0) {
+        float hv[NCH > 0 ? NCH : 1][4];
+        float s = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            h_at((c * 64 + lane) * 4, hv[c], 4);
+            s += (hv[c][0] + hv[c][1]) + (hv[c][2] + hv[c][3]);
+        }
+        const float mean = wave_sum(s) / (float)W;
+        float q = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { const float d = hv[c][e] - mean; q = fmaf(d, d, q); }
+        const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)W + a.ln_eps);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int j = (c * 64 + lane) * 4;
+            store4<float>(hrow + j, hv[c]);
+            emit(j, hv[c], 4, mean, rstd);
+        }
+    } else {
+        float s = 0.f, v[4];
+        for (int j = lane; j < W; j += 64) { h_at(j, v, 1); hrow[j] = v[0]; s += v[0]; }   // pass 1 writes h
+        const float mean = wave_sum(s) / (float)W;
+        float q = 0.f;
+        for (int j = lane; j < W; j += 64) { const float d = hrow[j] - mean; q = fmaf(d, d, q); }
+        const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)W + a.ln_eps);
+        for (int j = lane; j < W; j += 64) { v[0] = hrow[j]; emit(j, v, 1, mean, rstd); }
     }
 }
 
-hipError_t launch_ln_mod(const float* h, const void* mod, int ldm, int mod_is_f32, void* u, int out_mode,
-                         float ln_eps, int64_t R, int W, hipStream_t st) {
-    if (R == 0) return hipSuccess;
-    const int rows_per_block = 4;
-    dim3 grid((unsigned)((R + rows_per_block - 1) / rows_per_block)), block(64 * rows_per_block);
-    if (out_mode == LN_OUT_F32 && mod_is_f32)
-        hipLaunchKernelGGL((k_ln_mod<float, float, OUT_SAME>), grid, block, 0, st, h, (const float*)mod, ldm, (float*)u, ln_eps, R, W);
-    else if (out_mode == LN_OUT_BF16 && !mod_is_f32)
-        hipLaunchKernelGGL((k_ln_mod<bf16_t, bf16_t, OUT_SAME>), grid, block, 0, st, h, (const bf16_t*)mod, ldm, (bf16_t*)u, ln_eps, R, W);
-    else if (out_mode == LN_OUT_BF16_SPLIT && mod_is_f32)
-        hipLaunchKernelGGL((k_ln_mod<float, bf16_t, OUT_SPLIT>), grid, block, 0, st, h, (const float*)mod, ldm, (bf16_t*)u, ln_eps, R, W);
-    else
-        return hipErrorInvalidValue;
-    return hipGetLastError();
+template <typename TAct, int MODE, int D>
+static void launch_block_pre_nch(const BlockPreArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+    const bool vec = a.W % 256 == 0 && a.ldg % 4 == 0 && a.ldm % 4 == 0;
+    switch (vec ? a.W / 256 : 0) {
+        case 2: hipLaunchKernelGGL((k_block_pre<TAct, MODE, D, 2>), grid, block, 0, st, a); break;
+        case 3: hipLaunchKernelGGL((k_block_pre<TAct, MODE, D, 3>), grid, block, 0, st, a); break;
+        case 4: hipLaunchKernelGGL((k_block_pre<TAct, MODE, D, 4>), grid, block, 0, st, a); break;
+        case 5: hipLaunchKernelGGL((k_block_pre<TAct, MODE, D, 5>), grid, block, 0, st, a); break;
+        case 6: hipLaunchKernelGGL((k_block_pre<TAct, MODE, D, 6>), grid, block, 0, st, a); break;
+        case 8: hipLaunchKernelGGL((k_block_pre<TAct, MODE, D, 8>), grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL((k_block_pre<TAct, MODE, D, 0>), grid, block, 0, st, a); break;
+    }
+}
+
+template <typename TAct, int MODE>
+static hipError_t launch_block_pre_d(const BlockPreArgs& a, dim3 grid, dim3 block, hipStream_t st) {
+    if (MODE != PRE_FIRST) { launch_block_pre_nch<TAct, MODE, 4>(a, grid, block, st); return hipSuccess; }
+    switch (a.D) {
+        case 4: launch_block_pre_nch<TAct, MODE, 4>(a, grid, block, st); break;
+        case 8: launch_block_pre_nch<TAct, MODE, 8>(a, grid, block, st); break;
+        case 16: launch_block_pre_nch<TAct, MODE, 16>(a, grid, block, st); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_block_pre(const BlockPreArgs& a, hipStream_t st) {
+    if (a.R == 0) return hipSuccess;
+    dim3 grid((unsigned)((a.R + 3) / 4)), block(256);
+    hipError_t e = hipErrorInvalidValue;
+    if (a.act == ACT_BF16) {
+        if (a.mode == PRE_FIRST) e = launch_block_pre_d<bf16_t, PRE_FIRST>(a, grid, block, st);
+        else if (a.mode == PRE_MIDDLE) e = launch_block_pre_d<bf16_t, PRE_MIDDLE>(a, grid, block, st);
+        else if (a.mode == PRE_FINAL) e = launch_block_pre_d<bf16_t, PRE_FINAL>(a, grid, block, st);
+    } else {
+        if (a.mode == PRE_FIRST) e = launch_block_pre_d<float, PRE_FIRST>(a, grid, block, st);
+        else if (a.mode == PRE_MIDDLE) e = launch_block_pre_d<float, PRE_MIDDLE>(a, grid, block, st);
+        else if (a.mode == PRE_FINAL) e = launch_block_pre_d<float, PRE_FINAL>(a, grid, block, st);
+    }
+    return e != hipSuccess ? e : hipGetLastError();
 }
 
 // ---------------------------------------------------------------- end of a denoising step

@@ -72,7 +72,7 @@ enum { ACT_F32 = 0, ACT_BF16 = 1 };
 // Epilogues of the GEMM C = A * B^T (+ bias)
 enum { EPI_BIAS = 0,        // C = acc + bias
        EPI_BIAS_SILU = 1,   // C = silu(acc + bias)
-       EPI_GATE_RES = 2 };  // C(fp32) += gate * (acc + bias)
+       EPI_GATE_RES = 2 };  // C(fp32) += gate * (acc + bias)   (stage-wise hook only)
 
 struct GemmArgs {
     const void* A; int lda;        // [M,K] activations (fp32 or bf16)
@@ -90,12 +90,19 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st);
 
 // s = silu(E_t + e)
 hipError_t launch_cond_silu(const float* e, const float* time_emb_t, void* s, int act, int64_t R, int W, hipStream_t st);
-// h = W_in x + b_in
-hipError_t launch_inproj(const float* x, const float* w, const float* b, float* h, int64_t R, int D, int W, hipStream_t st);
-// u = LN(h)*(1+scale)+shift with (shift,scale) = mod[:, 0:W], mod[:, W:2W]
-enum { LN_OUT_F32 = 0, LN_OUT_BF16 = 1, LN_OUT_BF16_SPLIT = 2 };   // split: [hi | lo] bf16, 2W per row
-hipError_t launch_ln_mod(const float* h, const void* mod, int ldm, int mod_is_f32, void* u, int out_mode,
-                         float ln_eps, int64_t R, int W, hipStream_t st);
+// start of a block: residual of the previous block (or the input projection), LN, modulation
+struct BlockPreArgs {
+    int mode;                  // 0 first block, 1 middle, 2 after the last block (see elementwise.hip)
+    int act;                   // ACT_F32 | ACT_BF16: type of y, gate, mod (modes 0,1) and u
+    float* h;                  // [R,W] fp32 residual stream, read (modes 1,2) and written
+    const void* y;             // [R,W] output of the previous block's second linear layer
+    const void* gate; int ldg; // [R,ldg] gate of the previous block
+    const void* mod; int ldm;  // shift at columns [0,W), scale at [W,2W); fp32 in mode 2
+    void* u;                   // [R,W] (mode 2 with bf16: [R,2W] = [hi | lo])
+    const float* x; const float* w_in; const float* b_in;   // mode 0: x [R,D], W_in [W,D], b_in [W]
+    float ln_eps; int64_t R; int W; int D;
+};
+hipError_t launch_block_pre(const BlockPreArgs& a, hipStream_t st);
 
 struct TransArgs {
     const float* o; int ldo;   // [R, ldo] fp32 output projection: columns [0,D) eps part, [D,2D) v
