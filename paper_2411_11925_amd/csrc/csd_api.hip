@@ -173,24 +173,38 @@ TransArgs trans_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
     return f;
 }
 
-// side stream (default priority) and its fork/join events, one set per device, created on
-// first use and kept until the process ends.  CSD_SINGLE_STREAM=1 keeps everything on the
-// caller's stream.
-struct SideStream { hipStream_t stream = nullptr; hipEvent_t fork = nullptr, join = nullptr; bool ok = false; };
+// Side streams (default priority) with their fork/join events, one set per device, created
+// on first use and kept until the process ends.  CSD_SINGLE_STREAM=1 keeps everything on
+// the caller's stream; CSD_ROW_CHUNKS=n (1..4) sets how many row chunks run as separate chains.
+constexpr int MAX_SIDE = 7;
+struct SideStreams {
+    hipStream_t stream[MAX_SIDE] = {};
+    hipEvent_t join[MAX_SIDE] = {};
+    hipEvent_t fork = nullptr;
+    bool ok = false;
+};
 
-SideStream* side_stream(int device) {
-    static SideStream streams[16];
+SideStreams* side_streams(int device) {
+    static SideStreams sets[16];
     static int disabled = -1;
     if (disabled < 0) { const char* e = getenv("CSD_SINGLE_STREAM"); disabled = (e && *e == '1') ? 1 : 0; }
     if (disabled || device < 0 || device >= 16) return nullptr;
-    SideStream& s = streams[device];
+    SideStreams& s = sets[device];
     if (!s.ok) {
-        if (hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
         if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-        if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+        for (int i = 0; i < MAX_SIDE; ++i) {
+            if (hipStreamCreateWithFlags(&s.stream[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
+            if (hipEventCreateWithFlags(&s.join[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+        }
         s.ok = true;
     }
     return &s;
+}
+
+int row_chunks_setting() {
+    static int v = -1;
+    if (v < 0) { const char* e = getenv("CSD_ROW_CHUNKS"); v = (e && *e) ? atoi(e) : 0; if (v < 0 || v > 4) v = 0; }
+    return v;
 }
 
 struct DeviceGuard {
@@ -367,9 +381,11 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
 
 size_t csd_workspace_bytes(const csd_head_t* draft, const csd_head_t* target, int64_t n_rows) {
     if (n_rows < 0 || (!draft && !target)) return 0;
+    // room for up to 4 row chunks, each rounded up to 256 rows (see csd_denoise_lockstep)
+    const int64_t padded = n_rows + 4 * 256;
     size_t n = 256;
-    if (draft) n += head_ws_bytes(draft, n_rows);
-    if (target) n += head_ws_bytes(target, n_rows);
+    if (draft) n += head_ws_bytes(draft, padded) + 4 * 16 * 256;
+    if (target) n += head_ws_bytes(target, padded) + 4 * 16 * 256;
     return n;
 }
 
@@ -391,43 +407,72 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, cons
                     csd_workspace_bytes(draft, target, R));
     hipStream_t st = (hipStream_t)hip_stream;
     const int D = draft->D, T = draft->T;
-    HeadWs wq, wp;
-    char* p = carve(draft, R, (char*)workspace, &wq);
-    carve(target, R, p, &wp);
 
-    // The two heads never exchange data inside the T steps (they only share the noise,
-    // which each regenerates from the counters), so the draft chain runs on a side
-    // stream next to the target chain: one chain's memory-bound kernels and epilogues
-    // fill the gaps of the other's MFMA loops.  Fork and join are events on the caller's
-    // stream; the call still does not synchronise the host.
-    HIP_TRY(launch_init_x(wq.x, wp.x, wq.acc, wp.acc, R, D, T, seed, row_offset, st));
-    SideStream* side = side_stream(draft->device);
-    hipStream_t sq = st;
-    if (side) {
-        HIP_TRY(hipEventRecord(side->fork, st));
-        HIP_TRY(hipStreamWaitEvent(side->stream, side->fork, 0));
-        sq = side->stream;
-    }
-    HIP_TRY(cond_embed(draft, z_q, wq, R, sq));
-    HIP_TRY(cond_embed(target, z_p, wp, R, st));
-    for (int t = T; t >= 1; --t) {
+    // Rows never interact, and the two heads only share the noise (which each regenerates
+    // from the counters), so the call is cut into independent chains - (row chunk, head) -
+    // that run on their own streams.  One chain's memory-bound kernels and GEMM epilogues
+    // then fill the gaps of another chain's MFMA loops.  Chunks are multiples of 256 rows
+    // (the GEMM tile height), so every result is bit-identical to a single-chain run.
+    // Fork and join are events on the caller's stream; the host is never synchronised.
+    SideStreams* side = side_streams(draft->device);
+    int n_chunks = row_chunks_setting();
+    if (n_chunks == 0) n_chunks = (R >= 8192) ? 2 : 1;
+    if (!side) n_chunks = 1;
+    int64_t chunk_rows = ((R + n_chunks - 1) / n_chunks + 255) / 256 * 256;
+    if (chunk_rows >= R) { n_chunks = 1; chunk_rows = R; }
+    n_chunks = (int)((R + chunk_rows - 1) / chunk_rows);
+
+    struct Chain { const csd_head* hd; HeadWs ws; int64_t r0, n; hipStream_t s; int which; };
+    Chain chains[8];
+    int n_chains = 0;
+    char* wp_ = (char*)workspace;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t r0 = c * chunk_rows, n = (R - r0 < chunk_rows) ? R - r0 : chunk_rows;
         for (int which = 0; which < 2; ++which) {
-            const csd_head* hd = which ? target : draft;
-            const HeadWs& ws = which ? wp : wq;
-            hipStream_t s = which ? st : sq;
-            HIP_TRY(head_body(hd, ws, t, R, s));
-            TransArgs f = trans_args(hd, ws, t, R);
-            f.seed = seed; f.row_offset = row_offset; f.tau = temperature;
-            f.summary = summary; f.is_target = which;
-            HIP_TRY(launch_transition(f, s));
+            Chain& ch = chains[n_chains];
+            ch.hd = which ? target : draft; ch.r0 = r0; ch.n = n; ch.which = which;
+            wp_ = carve(ch.hd, n, wp_, &ch.ws);
+            ch.s = (n_chains == 0 || !side) ? st : side->stream[n_chains - 1];
+            ++n_chains;
         }
     }
-    if (side) {
-        HIP_TRY(hipEventRecord(side->join, side->stream));
-        HIP_TRY(hipStreamWaitEvent(st, side->join, 0));
+    if (side && n_chains > 1) {
+        HIP_TRY(hipEventRecord(side->fork, st));
+        for (int i = 1; i < n_chains; ++i) HIP_TRY(hipStreamWaitEvent(chains[i].s, side->fork, 0));
     }
-    const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
-    HIP_TRY(launch_finish_summary(summary, wq.acc, wp.acc, ref_diff, R, D, st));
+    for (int i = 0; i < n_chains; i += 2) {     // x_T and the accumulators of both heads of a chunk
+        Chain& q = chains[i]; Chain& pch = chains[i + 1];
+        HIP_TRY(launch_init_x(q.ws.x, pch.ws.x, q.ws.acc, pch.ws.acc, q.n, D, T, seed, row_offset + q.r0, q.s));
+        if (q.s != pch.s) {                     // the target chain starts after its x_T is written
+            HIP_TRY(hipEventRecord(side->join[i], q.s));
+            HIP_TRY(hipStreamWaitEvent(pch.s, side->join[i], 0));
+        }
+    }
+    for (int i = 0; i < n_chains; ++i) {
+        Chain& ch = chains[i];
+        HIP_TRY(cond_embed(ch.hd, (ch.which ? z_p : z_q) + ch.r0 * ch.hd->C, ch.ws, ch.n, ch.s));
+    }
+    for (int t = T; t >= 1; --t) {
+        for (int i = 0; i < n_chains; ++i) {
+            Chain& ch = chains[i];
+            HIP_TRY(head_body(ch.hd, ch.ws, t, ch.n, ch.s));
+            TransArgs f = trans_args(ch.hd, ch.ws, t, ch.n);
+            f.seed = seed; f.row_offset = row_offset + ch.r0; f.tau = temperature;
+            f.summary = summary + ch.r0 * (5 * D + 1); f.is_target = ch.which;
+            HIP_TRY(launch_transition(f, ch.s));
+        }
+    }
+    if (side && n_chains > 1) {
+        for (int i = 1; i < n_chains; ++i) {
+            HIP_TRY(hipEventRecord(side->join[i - 1], chains[i].s));
+            HIP_TRY(hipStreamWaitEvent(st, side->join[i - 1], 0));
+        }
+    }
+    for (int i = 0; i < n_chains; i += 2) {
+        const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
+        HIP_TRY(launch_finish_summary(summary + chains[i].r0 * (5 * D + 1), chains[i].ws.acc, chains[i + 1].ws.acc,
+                                      ref_diff, chains[i].n, D, st));
+    }
     return CSD_OK;
 }
 
