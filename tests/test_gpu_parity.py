@@ -282,3 +282,70 @@ def test_tiny_workload_end_to_end_bf16(B, out_scale):
     wl = S.WORKLOADS["tiny"].with_(gamma=2, gemm_dtype="bf16", out_scale=out_scale)
     res = _end_to_end(B, wl, 150, H.BF16_TOL, dtype="bf16", check_decisions=False)
     assert res["agree"] > (0.8 if out_scale < 0.5 else 0.0)
+
+
+# ------------------------------------------- full-size runs, bench configuration ----
+def _sampled_rows_check(B, wl, R, sample_blocks, tol, check_decisions):
+    """Run the whole path at R rows in the launch configuration bench.py times (default
+    chains and tile choice), then recompute sampled 64-row blocks one by one on the
+    oracle (rows are keyed by their global index) and compare."""
+    gamma, D, seed = wl.gamma, 16, wl.seed
+    G = R // gamma
+    drf, tgt, blobs = H.oracle_heads(wl)
+    dq, dp = H.device_heads(B, wl, blobs)
+    zq, zp = wl.conds(R)
+    summ = B.csd_denoise_lockstep(dq, dp, _t(zq), _t(zp), G, gamma, seed)
+    n_g, ell_g, mask_g = B.csd_verify(summ, G, gamma, D, seed)
+    tok_g, nout_g, trips_g, flags_g = B.csd_resample(summ, n_g, G, gamma, D, seed)
+    torch.cuda.synchronize()
+    sg, n_g, mask_g = summ.cpu().numpy(), n_g.cpu().numpy(), mask_g.cpu().numpy()
+    tok_g, nout_g, trips_g = tok_g.cpu().numpy(), nout_g.cpu().numpy(), trips_g.cpu().numpy()
+    # properties that hold at any size
+    assert np.all(np.isfinite(sg))
+    assert np.all((n_g >= 0) & (n_g <= gamma)) and np.all(nout_g == np.minimum(n_g + 1, gamma))
+    first_rej = np.where(mask_g.reshape(G, gamma).all(1), gamma, np.argmin(mask_g.reshape(G, gamma), axis=1))
+    assert np.array_equal(n_g, first_rej)
+    assert np.all((trips_g > 0) == (n_g < gamma))
+    for g in range(0, G, max(1, G // 50)):
+        assert np.array_equal(tok_g[g, :n_g[g]], sg[g * gamma: g * gamma + n_g[g], 4 * D:5 * D])
+        assert np.all(tok_g[g, nout_g[g]:] == 0)
+    again = B.csd_denoise_lockstep(dq, dp, _t(zq), _t(zp), G, gamma, seed)
+    assert torch.equal(again, summ)                      # run-to-run determinism at full size
+    agree = []
+    for r0 in sample_blocks:
+        zq_s, zp_s = wl.conds(64, r0)
+        assert np.array_equal(zq_s, zq[r0:r0 + 64])
+        s_o, _ = O.denoise_lockstep(drf, tgt, zq_s, zp_s, seed, row_offset=r0)
+        assert H.rel_err(sg[r0:r0 + 64, 4 * D:5 * D], s_o[:, 4 * D:5 * D]) < tol, "tokens of rows %d.." % r0
+        assert H.rel_err(sg[r0:r0 + 64, 0:D], s_o[:, 0:D]) < tol
+        n_o, ell_o, mask_o, log_u = O.verify(s_o, 64 // gamma, gamma, seed, r0)
+        agree.append((mask_g[r0:r0 + 64].astype(bool) == mask_o.astype(bool)).mean())
+        if check_decisions:
+            H.decisions_match(mask_g[r0:r0 + 64], ell_o, log_u, gamma)
+    dq.free(); dp.free()
+    return float(np.mean(agree)), float(mask_g.mean())
+
+
+def test_mar256_full_size_bf16_sampled_rows(B):
+    wl = S.WORKLOADS["mar256"]
+    R = wl.rows_total
+    agree, acc = _sampled_rows_check(B, wl, R, [0, 8192 - 64, 8192, R - 64], H.BF16_TOL, check_decisions=False)
+    assert agree > 0.9 and 0.15 < acc < 0.7
+
+
+def test_mar256_latency_shape_f32(B):
+    """One verify step of the 256x256-shaped workload (64 images x 4 draft tokens) in fp32:
+    tokens to 1e-4 and decisions bit-exact outside the band."""
+    wl = S.WORKLOADS["mar256"].with_(gemm_dtype="f32")
+    _sampled_rows_check(B, wl, wl.rows_per_verify_step, [0, 192], H.F32_TOL, check_decisions=True)
+
+
+def test_large_head_bf16_sampled_rows(B):
+    wl = S.WORKLOADS["large"]
+    _sampled_rows_check(B, wl, 2048 + 256, [0, 2048], H.BF16_TOL, check_decisions=False)
+
+
+def test_reject_heavy_ragged_rows_bf16(B):
+    """gamma = 8, a row count that is no multiple of any tile (ragged tail)."""
+    wl = S.WORKLOADS["reject"]
+    _sampled_rows_check(B, wl, 8 * 300, [0, 2304], H.BF16_TOL, check_decisions=False)
