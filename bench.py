@@ -25,6 +25,25 @@ def head_flops_per_row_step(sh):
     return (10 * L + 4) * W * W + 6 * D * W
 
 
+def measured_traffic(workload, dtype, rows):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter
+    summary of this same workload (profiles/), or None if there is none for it."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_mod_gemm_traffic.txt" % (workload, dtype))
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if ":" in line and not line.startswith("#"):
+            k, v = line.split(":", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except (ValueError, IndexError):
+                pass
+    if vals.get("rows_per_step") != rows or "traffic_bytes_per_launch" not in vals:
+        return None
+    return vals["traffic_bytes_per_launch"]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -34,6 +53,9 @@ def main():
     ap.add_argument("--dtype", default=None, choices=[None, "bf16", "f32"])
     ap.add_argument("--rows", type=int, default=0, help="rows per step (default: the whole workload)")
     ap.add_argument("--oracle-rows", type=int, default=128, help="rows of the CPU-oracle sample (0: skip)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed steps, copy 256 MiB device to device once (a kernel of known "
+                         "traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py measures one GPU: every box of this build has one MI355X and the path has no "
@@ -72,7 +94,7 @@ def main():
         step()
     torch.cuda.synchronize()
     launches_per_step = 2 * wl.n_steps * (ds.n_blocks + wl.target.n_blocks) // 2
-    B.csd_profile_enable(min(a.steps * launches_per_step + 16, 1 << 18))
+    B.csd_profile_enable(min(4 * a.steps * launches_per_step + 16, 1 << 18))   # up to 4 row chunks per call
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
@@ -84,12 +106,23 @@ def main():
     ms = ev0.elapsed_time(ev1)
     k_ms, k_n, k_flops = B.csd_profile_read()
     B.csd_profile_enable(0)
+    if a.calibration_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     flops_row = wl.n_steps * (head_flops_per_row_step(wl.target) + head_flops_per_row_step(ds)) \
         + 2 * wl.target.cond_dim * (wl.target.width + ds.width)
     tokens_per_s = R * a.steps / (ms / 1e3)
     achieved = (k_flops / k_n) / (k_ms / k_n / 1e3) / 1e12 if k_n else 0.0
     peak = PEAK[dtype]
+    # modulation GEMM per launch: reads s [M,W] and the weights [3W,W], writes [M,3W]; bf16 = 2 bytes
+    esz = 2 if dtype == "bf16" else 4
+    m_launch = k_flops / k_n / (3 * (wl.target.width ** 2 + ds.width ** 2)) if k_n else 0   # mean rows per launch
+    alg_bytes = esz * (m_launch * (wl.target.width + ds.width) / 2 * 4
+                       + 3 * (wl.target.width ** 2 + ds.width ** 2) / 2) if k_n else None
     mask_h, trips_h, nacc_h = mask.cpu().numpy(), trips.cpu().numpy(), n_acc.cpu().numpy()
     res = {
         "metric": "verified tokens/sec (denoise+verify+resample)", "value": tokens_per_s, "unit": "tokens/s",
@@ -108,7 +141,9 @@ def main():
                        "resample_trips_max": int(trips_h.max()), "cap_flags": int((flags.cpu().numpy() & 1).sum())},
         "roofline": {"bound": "mfma" if dtype == "bf16" else "alu", "kernel": "modulation GEMM [R,W]x[W,3W]",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "launches_timed": k_n, "avg_launch_ms": k_ms / k_n if k_n else None, "traffic": None},
+                     "launches_timed": k_n, "avg_launch_ms": k_ms / k_n if k_n else None,
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "traffic": measured_traffic(wl.name, dtype, R)},
     }
 
     if a.oracle_rows > 0:
