@@ -22,7 +22,7 @@ What it computes, in the paper's order and notation (numpy, float64):
 
 The diffusion head itself is not defined by the paper ("a neural network with
 parameter theta", Sec. 3.1); the adaLN residual MLP used here is this build's
-own definition and is documented in the design doc.  Its forward pass therefore has
+own definition (written out in class Head below).  Its forward pass therefore has
 no pin against the paper: PARITY UNPINNED against the paper for `head_forward`
 (it is pinned by internal invariants and an independent scalar-loop
 re-implementation in the tests).

@@ -120,7 +120,7 @@ class Workload:
     tokens_per_image: int
     rho: float | None            # cond correlation (None: additive 0.1 noise)
     out_scale: float             # std multiplier of the output layer (acceptance knob)
-    eps_skip_gain: float         # input-to-output skip of the head
+    eps_skip_gain: float         # input-to-output skip of the head: eps_hat = gain*sqrt(1-abar_t)*x_t + o
     gemm_dtype: str              # "f32" | "bf16"
     seed: int
 
