@@ -124,46 +124,72 @@ hipError_t cond_embed(const csd_head* hd, const float* z, const HeadWs& ws, int6
     return launch_gemm_f32(g, st);
 }
 
-// everything of step t up to (not including) the transition kernel: leaves o ready
-hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hipStream_t st) {
+// One denoising step of one head is cut into phases p = 0 .. L+1, each a GEMM part followed
+// by an elementwise part (preceded once by s = SiLU(E_t + e)):
+//   G_0: mod_0                         E_0: block_pre(first)
+//   G_p: fc1_{p-1}, fc2_{p-1}, mod_p   E_p: block_pre(middle)        (1 <= p < L)
+//   G_L: fc1_{L-1}, fc2_{L-1}, fmod    E_L: block_pre(final)
+//   G_{L+1}: output projection         E_{L+1}: transition (by the caller)
+hipError_t phase_cond(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hipStream_t se) {
+    const int act = hd->cfg.gemm_dtype == CSD_BF16 ? ACT_BF16 : ACT_F32;
+    return launch_cond_silu(ws.e, hd->d_time_emb + (size_t)t * hd->W, ws.s, act, R, hd->W, se);
+}
+
+hipError_t phase_gemm(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hipStream_t sg) {
     const int W = hd->W, L = hd->L;
     const bool b16 = hd->cfg.gemm_dtype == CSD_BF16;
-    const int act = b16 ? ACT_BF16 : ACT_F32;
-    const size_t asz = b16 ? 2 : 4;
     hipError_t e;
-    if ((e = launch_cond_silu(ws.e, hd->d_time_emb + (size_t)t * W, ws.s, act, R, W, st)) != hipSuccess) return e;
-    BlockPreArgs bp{};
-    bp.act = act; bp.h = ws.h; bp.y = ws.y; bp.u = ws.u; bp.ln_eps = hd->ln_eps; bp.R = R; bp.W = W; bp.D = hd->D;
-    bp.x = ws.x; bp.w_in = hd->in.w; bp.b_in = hd->in.b;
-    for (int l = 0; l <= L; ++l) {
-        // modulation of block l (l = L: the final one, kept in fp32 because it feeds eps_hat directly)
-        void* mod = (l == L) ? (void*)ws.fm : ws.mod[l & 1];
-        const Linear& ml = (l == L) ? hd->fmod : hd->mod[l];
-        GemmArgs g{};
-        g.M = (int)R; g.K = W; g.A = ws.s; g.lda = W;
-        g.B = b16 ? (const void*)ml.w16 : (const void*)ml.w; g.bias = ml.b;
-        g.C = mod; g.N = ml.n_out; g.ldc = ml.n_out; g.epi = EPI_BIAS; g.c_is_f32 = (l == L) ? 1 : 0;
-        if ((e = (l == L) ? gemm(hd, g, st) : gemm_timed(hd, g, st)) != hipSuccess) return e;
-        // residual of block l-1 (or the input projection), LN, modulation -> u
-        bp.mode = (l == 0) ? 0 : (l == L ? 2 : 1);
-        bp.mod = mod; bp.ldm = ml.n_out;
-        if (l > 0) { bp.gate = (const char*)ws.mod[(l - 1) & 1] + (size_t)2 * W * asz; bp.ldg = 3 * W; }
-        if ((e = launch_block_pre(bp, st)) != hipSuccess) return e;
-        if (l == L) break;
-        // a = silu(fc1 u);  y = fc2 a
+    GemmArgs g{};
+    g.M = (int)R; g.K = W; g.lda = W;
+    if (p == L + 1) {
+        // o = Lin_out(u), padded to 64 columns.  In bf16 mode u is the [hi | lo] pair against [w | w].
+        g.N = 64; g.K = b16 ? 2 * W : W; g.A = ws.u; g.lda = g.K;
+        g.B = b16 ? (const void*)hd->out_pad.w16 : (const void*)hd->out_pad.w; g.bias = hd->out_pad.b;
+        g.C = ws.o; g.ldc = 64; g.epi = EPI_BIAS; g.c_is_f32 = 1;
+        return gemm(hd, g, sg);
+    }
+    if (p >= 1) {
+        const int l = p - 1;           // a = silu(fc1 u);  y = fc2 a
         g.A = ws.u; g.B = b16 ? (const void*)hd->fc1[l].w16 : (const void*)hd->fc1[l].w;
         g.bias = hd->fc1[l].b; g.C = ws.a; g.ldc = W; g.N = W; g.epi = EPI_BIAS_SILU; g.c_is_f32 = 0;
-        if ((e = gemm(hd, g, st)) != hipSuccess) return e;
+        if ((e = gemm(hd, g, sg)) != hipSuccess) return e;
         g.A = ws.a; g.B = b16 ? (const void*)hd->fc2[l].w16 : (const void*)hd->fc2[l].w;
         g.bias = hd->fc2[l].b; g.C = ws.y; g.epi = EPI_BIAS;
-        if ((e = gemm(hd, g, st)) != hipSuccess) return e;
+        if ((e = gemm(hd, g, sg)) != hipSuccess) return e;
     }
-    // o = Lin_out(u), padded to 64 columns.  In bf16 mode u is the [hi | lo] pair against [w | w].
-    GemmArgs go{};
-    go.M = (int)R; go.N = 64; go.K = b16 ? 2 * W : W; go.A = ws.u; go.lda = go.K;
-    go.B = b16 ? (const void*)hd->out_pad.w16 : (const void*)hd->out_pad.w; go.bias = hd->out_pad.b;
-    go.C = ws.o; go.ldc = 64; go.epi = EPI_BIAS; go.c_is_f32 = 1;
-    return gemm(hd, go, st);
+    // modulation of block p (p = L: the final one, kept in fp32 because it feeds eps_hat directly)
+    const Linear& ml = (p == L) ? hd->fmod : hd->mod[p];
+    g.A = ws.s; g.B = b16 ? (const void*)ml.w16 : (const void*)ml.w; g.bias = ml.b;
+    g.C = (p == L) ? (void*)ws.fm : ws.mod[p & 1]; g.N = ml.n_out; g.ldc = ml.n_out; g.epi = EPI_BIAS;
+    g.c_is_f32 = (p == L) ? 1 : 0;
+    return (p == L) ? gemm(hd, g, sg) : gemm_timed(hd, g, sg);
+}
+
+// elementwise part of phases 0..L (residual or input projection, LN, modulation -> u)
+hipError_t phase_elem(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hipStream_t se) {
+    const int W = hd->W, L = hd->L;
+    const bool b16 = hd->cfg.gemm_dtype == CSD_BF16;
+    const size_t asz = b16 ? 2 : 4;
+    BlockPreArgs bp{};
+    bp.act = b16 ? ACT_BF16 : ACT_F32; bp.h = ws.h; bp.y = ws.y; bp.u = ws.u; bp.ln_eps = hd->ln_eps;
+    bp.R = R; bp.W = W; bp.D = hd->D;
+    bp.x = ws.x; bp.w_in = hd->in.w; bp.b_in = hd->in.b; bp.w_in_t = hd->d_in_t;
+    bp.mode = (p == 0) ? 0 : (p == L ? 2 : 1);
+    bp.mod = (p == L) ? (const void*)ws.fm : (const void*)ws.mod[p & 1];
+    bp.ldm = (p == L) ? 2 * W : 3 * W;
+    if (p > 0) { bp.gate = (const char*)ws.mod[(p - 1) & 1] + (size_t)2 * W * asz; bp.ldg = 3 * W; }
+    return launch_block_pre(bp, se);
+}
+
+// whole step on one stream (csd_head_eval)
+hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hipStream_t st) {
+    hipError_t e;
+    if ((e = phase_cond(hd, ws, t, R, st)) != hipSuccess) return e;
+    for (int p = 0; p <= hd->L + 1; ++p) {
+        if ((e = phase_gemm(hd, ws, p, R, st)) != hipSuccess) return e;
+        if (p <= hd->L && (e = phase_elem(hd, ws, p, R, st)) != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 TransArgs trans_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
@@ -178,8 +204,8 @@ TransArgs trans_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
 // the caller's stream; CSD_ROW_CHUNKS=n (1..4) sets how many row chunks run as separate chains.
 constexpr int MAX_SIDE = 7;
 struct SideStreams {
-    hipStream_t stream[MAX_SIDE] = {};
-    hipEvent_t join[MAX_SIDE] = {};
+    hipStream_t stream[MAX_SIDE + 1] = {};
+    hipEvent_t join[MAX_SIDE + 1] = {};
     hipEvent_t fork = nullptr;
     bool ok = false;
 };
@@ -192,7 +218,7 @@ SideStreams* side_streams(int device) {
     SideStreams& s = sets[device];
     if (!s.ok) {
         if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-        for (int i = 0; i < MAX_SIDE; ++i) {
+        for (int i = 0; i <= MAX_SIDE; ++i) {
             if (hipStreamCreateWithFlags(&s.stream[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
             if (hipEventCreateWithFlags(&s.join[i], hipEventDisableTiming) != hipSuccess) return nullptr;
         }
@@ -233,6 +259,7 @@ void csd_free_head(csd_head_t* h) {
     if (h->d_weights16) (void)hipFree(h->d_weights16);
     if (h->d_time_emb) (void)hipFree(h->d_time_emb);
     if (h->d_out_pad) (void)hipFree(h->d_out_pad);
+    if (h->d_in_t) (void)hipFree(h->d_in_t);
     delete h;
 }
 
@@ -323,6 +350,15 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
     lin(h->fmod, 2 * W, W, true);
     lin(h->out, 2 * D, W, false);
     if (off != n_floats) return bail(fail(CSD_EINVAL, "csd_init_head: internal layout mismatch"));
+    // input projection transposed to [D, W] (host transpose of the caller's blob)
+    {
+        const float* w_in_host = weights_host + ((size_t)W * CSD_TIME_FEATURES + W + (size_t)W * W + W + (size_t)W * C + W);
+        std::vector<float> tr((size_t)D * W);
+        for (int o = 0; o < W; ++o)
+            for (int d = 0; d < D; ++d) tr[(size_t)d * W + o] = w_in_host[(size_t)o * D + d];
+        INIT_TRY(hipMalloc((void**)&h->d_in_t, tr.size() * sizeof(float)));
+        INIT_TRY(hipMemcpy(h->d_in_t, tr.data(), tr.size() * sizeof(float), hipMemcpyHostToDevice));
+    }
     // output layer padded with zero rows to 64 outputs, so that it runs through the GEMM kernels
     {
         const size_t nw = (size_t)64 * W;
@@ -411,9 +447,11 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, cons
     // Rows never interact, and the two heads only share the noise (which each regenerates
     // from the counters), so the call is cut into independent chains - (row chunk, head) -
     // that run on their own streams.  One chain's memory-bound kernels and GEMM epilogues
-    // then fill the gaps of another chain's MFMA loops.  Chunks are multiples of 256 rows
-    // (the GEMM tile height), so every result is bit-identical to a single-chain run.
-    // Fork and join are events on the caller's stream; the host is never synchronised.
+    // then fill the gaps of another chain's MFMA loops.  (Tying the chains into a fixed
+    // GEMM/row-kernel pipeline with events was measured and is slower: every cross-stream
+    // hand-over costs more than the overlap it buys.)  Chunks are multiples of 256 rows (the
+    // GEMM tile height), so every result is bit-identical to a single-chain run.  Fork and
+    // join are events on the caller's stream; the host is never synchronised.
     SideStreams* side = side_streams(draft->device);
     int n_chunks = row_chunks_setting();
     if (n_chunks == 0) n_chunks = (R >= 8192) ? 2 : 1;
@@ -464,8 +502,8 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, cons
     }
     if (side && n_chains > 1) {
         for (int i = 1; i < n_chains; ++i) {
-            HIP_TRY(hipEventRecord(side->join[i - 1], chains[i].s));
-            HIP_TRY(hipStreamWaitEvent(st, side->join[i - 1], 0));
+            HIP_TRY(hipEventRecord(side->join[i], chains[i].s));
+            HIP_TRY(hipStreamWaitEvent(st, side->join[i], 0));
         }
     }
     for (int i = 0; i < n_chains; i += 2) {

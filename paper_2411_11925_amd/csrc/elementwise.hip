@@ -159,6 +159,86 @@ __global__ __launch_bounds__(256) void k_block_pre(BlockPreArgs a) {
     }
 }
 
+// First block, fast path: h = W_in x + b_in for FOUR rows per wave, so that each 16-byte
+// piece of the (transposed, [D][W]) input weights is loaded once per four rows; then the
+// same LN + modulation as above, row by row.
+template <typename TAct, int D, int NCH>
+__global__ __launch_bounds__(256) void k_block_first(BlockPreArgs a) {
+    constexpr int RPW = 4;
+    const int lane = threadIdx.x & 63;
+    const int64_t r0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RPW;
+    if (r0 >= a.R) return;
+    const int W = a.W;
+    float xr[RPW][D];
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) {
+        const int64_t r = (r0 + rr < a.R) ? r0 + rr : a.R - 1;
+#pragma unroll
+        for (int d = 0; d < D; ++d) xr[rr][d] = a.x[r * D + d];
+    }
+    float hv[RPW][NCH][4];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int j = (c * 64 + lane) * 4;
+        float b4[4];
+        load4<float>(a.b_in + j, b4);
+#pragma unroll
+        for (int rr = 0; rr < RPW; ++rr)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) hv[rr][c][e] = b4[e];
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            float w4[4];
+            load4<float>(a.w_in + (size_t)d * W + j, w4);
+#pragma unroll
+            for (int rr = 0; rr < RPW; ++rr)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) hv[rr][c][e] = fmaf(w4[e], xr[rr][d], hv[rr][c][e]);
+        }
+    }
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) {
+        const int64_t r = r0 + rr;
+        if (r >= a.R) break;
+        float s = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) s += (hv[rr][c][0] + hv[rr][c][1]) + (hv[rr][c][2] + hv[rr][c][3]);
+        const float mean = wave_sum(s) / (float)W;
+        float q = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { const float d = hv[rr][c][e] - mean; q = fmaf(d, d, q); }
+        const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)W + a.ln_eps);
+        const TAct* mrow = (const TAct*)a.mod + r * (size_t)a.ldm;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int j = (c * 64 + lane) * 4;
+            float sh[4], sc[4], uv[4];
+            load4<TAct>(mrow + j, sh); load4<TAct>(mrow + W + j, sc);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) uv[e] = fmaf((hv[rr][c][e] - mean) * rstd, 1.0f + sc[e], sh[e]);
+            store4<float>(a.h + r * W + j, hv[rr][c]);
+            store4<TAct>((TAct*)a.u + r * (size_t)W + j, uv);
+        }
+    }
+}
+
+template <typename TAct, int D>
+static bool launch_block_first(const BlockPreArgs& a, hipStream_t st) {
+    if (!a.w_in_t || a.W % 256 != 0 || a.ldm % 4 != 0) return false;
+    BlockPreArgs b = a;
+    b.w_in = a.w_in_t;
+    dim3 grid((unsigned)((a.R + 15) / 16)), block(256);
+    switch (a.W / 256) {
+        case 2: hipLaunchKernelGGL((k_block_first<TAct, D, 2>), grid, block, 0, st, b); return true;
+        case 3: hipLaunchKernelGGL((k_block_first<TAct, D, 3>), grid, block, 0, st, b); return true;
+        case 4: hipLaunchKernelGGL((k_block_first<TAct, D, 4>), grid, block, 0, st, b); return true;
+        case 5: hipLaunchKernelGGL((k_block_first<TAct, D, 5>), grid, block, 0, st, b); return true;
+        default: return false;
+    }
+}
+
 template <typename TAct, int MODE, int D>
 static void launch_block_pre_nch(const BlockPreArgs& a, dim3 grid, dim3 block, hipStream_t st) {
     const bool vec = a.W % 256 == 0 && a.ldg % 4 == 0 && a.ldm % 4 == 0;
@@ -177,9 +257,9 @@ template <typename TAct, int MODE>
 static hipError_t launch_block_pre_d(const BlockPreArgs& a, dim3 grid, dim3 block, hipStream_t st) {
     if (MODE != PRE_FIRST) { launch_block_pre_nch<TAct, MODE, 4>(a, grid, block, st); return hipSuccess; }
     switch (a.D) {
-        case 4: launch_block_pre_nch<TAct, MODE, 4>(a, grid, block, st); break;
-        case 8: launch_block_pre_nch<TAct, MODE, 8>(a, grid, block, st); break;
-        case 16: launch_block_pre_nch<TAct, MODE, 16>(a, grid, block, st); break;
+        case 4: if (!launch_block_first<TAct, 4>(a, st)) launch_block_pre_nch<TAct, MODE, 4>(a, grid, block, st); break;
+        case 8: if (!launch_block_first<TAct, 8>(a, st)) launch_block_pre_nch<TAct, MODE, 8>(a, grid, block, st); break;
+        case 16: if (!launch_block_first<TAct, 16>(a, st)) launch_block_pre_nch<TAct, MODE, 16>(a, grid, block, st); break;
         default: return hipErrorInvalidValue;
     }
     return hipSuccess;

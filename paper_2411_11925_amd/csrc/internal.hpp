@@ -55,6 +55,7 @@ struct csd_head {
     csd::Linear t1, t2, cond, in, fmod, out;
     csd::Linear out_pad;                 // output layer padded to 64 rows; bf16 copy is [w | w] (2W per row)
     float* d_out_pad = nullptr;          // storage of out_pad (fp32 w, b)
+    float* d_in_t = nullptr;             // input projection transposed to [D, W]
     std::vector<csd::Linear> mod, fc1, fc2;
     std::vector<csd::StepCoef> coef;     // [T+1], entry 0 unused
     std::vector<float> skip_sqrt;        // [T+1]: eps_skip_gain * sqrt(1 - abar_t)
@@ -102,6 +103,7 @@ struct BlockPreArgs {
     const void* mod; int ldm;  // shift at columns [0,W), scale at [W,2W); fp32 in mode 2
     void* u;                   // [R,W] (mode 2 with bf16: [R,2W] = [hi | lo])
     const float* x; const float* w_in; const float* b_in;   // mode 0: x [R,D], W_in [W,D], b_in [W]
+    const float* w_in_t;       // mode 0, optional: W_in transposed to [D,W] (enables the 4-rows-per-wave path)
     float ln_eps; int64_t R; int W; int D;
 };
 hipError_t launch_block_pre(const BlockPreArgs& a, hipStream_t st);
