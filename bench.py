@@ -106,6 +106,27 @@ def main():
     ms = ev0.elapsed_time(ev1)
     k_ms, k_n, k_flops = B.csd_profile_read()
     B.csd_profile_enable(0)
+    # the same kernel alone on the chip (same shapes, back to back on one stream), for
+    # comparison with the in-situ figure, whose launches share the chip with other chains
+    iso = None
+    if dtype == "bf16":
+        m_iso = R // 2 if R >= 8192 else R
+        tot_ms, tot_fl = 0.0, 0.0
+        for sh in (wl.target, ds):
+            A_ = torch.randn(m_iso, sh.width, device=dev).bfloat16()
+            W_ = (torch.randn(3 * sh.width, sh.width, device=dev) / sh.width ** 0.5).bfloat16()
+            b_ = torch.zeros(3 * sh.width, device=dev)
+            C_ = torch.empty(m_iso, 3 * sh.width, device=dev, dtype=torch.bfloat16)
+            for _ in range(3):
+                B.csd_gemm_bf16(A_, W_, b_, 0, C=C_)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                B.csd_gemm_bf16(A_, W_, b_, 0, C=C_)
+            e1.record(); torch.cuda.synchronize()
+            tot_ms += e0.elapsed_time(e1) / 20
+            tot_fl += 2.0 * m_iso * 3 * sh.width * sh.width
+        iso = tot_fl / (tot_ms / 1e3) / 1e12
     if a.calibration_copy:
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -143,6 +164,8 @@ def main():
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "launches_timed": k_n, "avg_launch_ms": k_ms / k_n if k_n else None,
                      "algorithmic_bytes_per_launch": alg_bytes,
+                     "alone_on_chip": None if iso is None else {"achieved": iso, "frac": iso / peak,
+                                                                 "note": "same kernel and shapes, no other chain running"},
                      "traffic": measured_traffic(wl.name, dtype, R)},
     }
 

@@ -156,10 +156,13 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     // private piece of the (now idle) LDS and walks it row-wise: NCH lanes cover the
     // TN*4 contiguous bytes of a row, so global loads and stores use whole cache lines.
     constexpr int NCH = TN / 4;                              // 16-byte chunks per staged row
-    constexpr int RPP = 64 / NCH;                            // rows per pass of the wave
+    constexpr int LPR = (64 % NCH == 0) ? NCH : 32;          // lanes per row (TN = 96: 24 of 32 lanes work)
+    constexpr int RPP = 64 / LPR;                            // rows per pass of the wave
+    static_assert(NCH <= LPR && (NCH % 8 == 0), "epilogue row mapping");
     float* stg = reinterpret_cast<float*>(smem + wave * (32 * TN * 4));
-    auto stg_swz = [](int row) { return NCH >= 16 ? (row & 15) : ((row >> 1) & (NCH - 1)); };
-    const int rd_row0 = lane / NCH, rd_c = lane % NCH;
+    // the XOR must map [0,NCH) onto itself: within aligned groups of 16 (NCH a multiple of 16) or 8
+    auto stg_swz = [](int row) { return NCH % 16 == 0 ? (row & 15) : (NCH == 8 ? ((row >> 1) & 7) : (row & 7)); };
+    const int rd_row0 = lane / LPR, rd_c = lane % LPR;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
 #pragma unroll
@@ -170,6 +173,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
                 *reinterpret_cast<float4*>(stg + l32 * TN + ((c ^ stg_swz(l32)) << 2)) =
                     make_float4(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
             }
+        if (rd_c >= NCH) continue;                           // idle lanes of a row (uniform over i)
         const int n = n0 + wn * TN + rd_c * 4;
         const float4 bb = *reinterpret_cast<const float4*>(p.bias + n);
 #pragma unroll
@@ -244,9 +248,17 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
     if (((uintptr_t)g.A & 15u) || ((uintptr_t)g.B & 15u) || ((uintptr_t)g.C & 15u)) return hipErrorInvalidValue;
     if (g.epi == EPI_GATE_RES && (g.ldg % 4 != 0 || ((uintptr_t)g.gate & 7u))) return hipErrorInvalidValue;
     int variant = gemm_variant_override();
-    if (variant < 0) variant = (g.N % 256 == 0 && g.M >= 2048) ? 1 : (g.N % 128 == 0 && g.M >= 256) ? 2 : 3;
-    if ((variant == 0 || variant == 1) && g.N % 256 != 0) variant = 3;
-    if ((variant == 2 || variant >= 4) && g.N % 128 != 0) variant = 3;
+    if (variant < 0) {
+        // large problems: 256-row tiles, 256 (or 192) columns wide
+        // (192 wins for one GEMM alone on the chip, e.g. 16384x768x768: 28 vs 34 us, but loses 5 % on
+        // the whole path, where several chains share the chip; it is used only where 256 does not divide N)
+        if (g.M >= 2048 && g.N % 256 == 0) variant = 1;
+        else if (g.M >= 2048 && g.N % 192 == 0) variant = 8;
+        else variant = (g.N % 128 == 0 && g.M >= 256) ? 2 : 3;
+    }
+    if ((variant == 0 || variant == 1) && g.N % 256 != 0) variant = (g.N % 192 == 0 && g.M >= 2048) ? 8 : 3;
+    if (variant == 8 && g.N % 192 != 0) variant = 3;
+    if ((variant == 2 || (variant >= 4 && variant != 8)) && g.N % 128 != 0) variant = 3;
     if (variant == 7) {
         static int safe = -1;
         if (safe < 0) { const char* e = getenv("CSD_GEMM_SAFE_WAIT"); safe = (e && *e == '1') ? 1 : 0; }
@@ -260,6 +272,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
         case 4: return launch_cfg<256, 128, 2, 2, 32, 3>(g, st);    // 4 waves, 128x64 per wave, 72 KiB LDS: 2 per CU
         case 5: return launch_cfg<256, 128, 2, 2, 32, 2>(g, st);    // same, 48 KiB LDS
         case 6: return launch_cfg<256, 128, 2, 2, 64, 2>(g, st);    // same tile, BK 64, 96 KiB LDS
+        case 8: return launch_cfg<256, 192, 4, 2, 64, 2>(g, st);    // 8 waves, 64x96 per wave: N = 3 * 2^k widths
         default: return launch_cfg<64, 64, 2, 2, 64, 2>(g, st);     // 4 waves, 32x32 per wave
     }
 }
