@@ -21,6 +21,7 @@
 // aligned A, B and leading dimensions; M is free (rows past M are clamped on load
 // and never stored).
 #include <cstdlib>
+#include <type_traits>
 
 #include "internal.hpp"
 
@@ -48,7 +49,10 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI, bool OUT_F32>
+// s_waitcnt with only lgkmcnt(0) set: this wave's LDS reads have returned
+__device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI, bool OUT_F32, bool PIPE = false>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;          // per-wave tile
@@ -85,9 +89,9 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     const int lr = lane / CPR, pc = lane % CPR;
     const int ld_swz = (CPR == 8) ? ((((wave & 1) << 2) + (lr >> 1)) & 7) : ((lr >> 2) & 3);
     const int ld_chunk = pc ^ ld_swz;
-    auto issue_loads = [&](int stage, int k0) {
+    auto issue_loads_part = [&](int stage, int k0, int i0, int i1) {
 #pragma unroll
-        for (int i = 0; i < GPW; ++i) {
+        for (int i = i0; i < i1; ++i) {
             const int g = wave + i * NW;               // rows RPL*g .. RPL*g+RPL-1 of the slab
             const int row = g * RPL + lr;
             const bf16_t* src;
@@ -102,6 +106,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
                                              16, 0, 0);
         }
     };
+    auto issue_loads = [&](int stage, int k0) { issue_loads_part(stage, k0, 0, GPW); };
 
     // ---- fragment read offsets (bytes) of this lane for the k16-steps of a slab
     const int swz = (l32 >> SH) & (CPR - 1);
@@ -119,10 +124,91 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    const int nk = p.K / BK;
+    if constexpr (PIPE) {
+        // ---- software-pipelined main loop (two stages of 64, at least 4 slabs).  Fragments are
+        // double-buffered in registers, so the LDS reads of k16-step kk+1 run under the MFMAs of
+        // step kk.  The ONE barrier per slab sits between steps 2 and 3: by then every wave holds
+        // the last fragments of slab s in registers, so the stage of slab s is free for slab s+2,
+        // and slab s+1 (requested one slab earlier) has landed, so its first fragments are read
+        // under the MFMAs of step 3 - no wave ever waits at a slab boundary with an empty MFMA
+        // pipe.  The requests for slab s+2 go out in two halves, after the barrier and in step 0
+        // of the next slab, so that no wave sits long in the queue of the load unit.
+        static_assert(BK == 64 && NST == 2 && GPW % 2 == 0, "pipelined loop: two stages of 64");
+        bf16x8 fa[2][FM], fb[2][FN];
+        auto read_frags = [&](auto buf_c, int stage, int kk) {
+            constexpr int buf = decltype(buf_c)::value;
+            const unsigned char* sa = smem + stage * STAGE_B + a_row_off + koff[kk];
+            const unsigned char* sb = smem + stage * STAGE_B + b_row_off + koff[kk];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) fa[buf][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sa + i * 32 * ROW_B));
+#pragma unroll
+            for (int j = 0; j < FN; ++j) fb[buf][j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sb + j * 32 * ROW_B));
+        };
+        // One k16-step in a pinned instruction order: behind each of the first FM+FN MFMAs
+        // (operands from buffer CUR) one fragment read of the NEXT step (into the other
+        // buffer), behind the last MFMAs the NL load requests [ld_i0, ld_i0+NL) of a later slab.
+        // The scheduling barriers keep the compiler from clustering them again.
+        auto step = [&](auto cur_c, auto read_c, int rd_stage, int rd_kk, auto nl_c, int ld_stage, int ld_k0, int ld_i0) {
+            constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1, NL = decltype(nl_c)::value;
+            constexpr bool READ = decltype(read_c)::value;
+            constexpr int NM = FM * FN, NR = FM + FN;
+            static_assert(NR <= NM && NL <= 2 * (NM - NR + 1), "step layout");
+            const unsigned char* sa = smem + rd_stage * STAGE_B + a_row_off + koff[rd_kk];
+            const unsigned char* sb = smem + rd_stage * STAGE_B + b_row_off + koff[rd_kk];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < NM; ++u) {
+                const int i = u / FN, j = u % FN;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[CUR][j], fa[CUR][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (READ && u < NR) {
+                    // fb first: the first MFMA of the next step then needs only reads 0 .. FN
+                    if (u < FN) fb[NXT][u] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sb + u * 32 * ROW_B));
+                    else fa[NXT][u - FN] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(sa + (u - FN) * 32 * ROW_B));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // load requests ride behind the MFMAs from index NR-1 on, two at a time
+                if (NL > 0 && u >= NR - 1) {
+                    const int l0 = (u - (NR - 1)) * 2;
+                    if (l0 < NL) {
+                        issue_loads_part(ld_stage, ld_k0, ld_i0 + l0, ld_i0 + (l0 + 2 < NL ? l0 + 2 : NL));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            }
+        };
+        typedef std::integral_constant<int, 0> I0;
+        typedef std::integral_constant<int, 1> I1;
+        typedef std::integral_constant<int, GPW / 2> IH;
+        typedef std::true_type RD;
+        auto slab = [&](auto first_c, auto next1_c, auto next2_c, int s) {
+            constexpr bool FIRST = decltype(first_c)::value, NEXT1 = decltype(next1_c)::value, NEXT2 = decltype(next2_c)::value;
+            const int st = s & 1;
+            if constexpr (!FIRST && NEXT1) step(I0{}, RD{}, st, 1, IH{}, st ^ 1, (s + 1) * BK, GPW / 2);
+            else step(I0{}, RD{}, st, 1, I0{}, 0, 0, 0);
+            step(I1{}, RD{}, st, 2, I0{}, 0, 0, 0);
+            step(I0{}, RD{}, st, 3, I0{}, 0, 0, 0);
+            if constexpr (NEXT1) wait_vmcnt<0>();
+            wait_lds_reads();
+            __builtin_amdgcn_s_barrier();
+            if constexpr (NEXT2) step(I1{}, RD{}, st ^ 1, 0, IH{}, st, (s + 2) * BK, 0);
+            else if constexpr (NEXT1) step(I1{}, RD{}, st ^ 1, 0, I0{}, 0, 0, 0);
+            else step(I1{}, std::false_type{}, 0, 0, I0{}, 0, 0, 0);
+        };
+        issue_loads(0, 0);
+        issue_loads(1, BK);
+        wait_vmcnt<GPW>();
+        __builtin_amdgcn_s_barrier();
+        read_frags(I0{}, 0, 0);
+        slab(std::true_type{}, std::true_type{}, std::true_type{}, 0);
+        for (int s = 1; s < nk - 2; ++s) slab(std::false_type{}, std::true_type{}, std::true_type{}, s);
+        slab(std::false_type{}, std::true_type{}, std::false_type{}, nk - 2);
+        slab(std::false_type{}, std::false_type{}, std::false_type{}, nk - 1);
+    } else {
     // ---- main loop: NST-deep ring of slabs.  At step kt the slabs kt .. kt+NST-2 are in
     // flight; wait for slab kt only, barrier (which also says everyone is done reading
     // slab kt-1), refill the stage of slab kt-1 with slab kt+NST-1, then compute slab kt.
-    const int nk = p.K / BK;
 #pragma unroll
     for (int s = 0; s < NST - 1; ++s)
         if (s < nk) issue_loads(s, s * BK);
@@ -148,6 +234,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
     }
+    }
     __syncthreads();      // all waves are done with the last slab: LDS is free for the epilogue
 
     // ---- epilogue.  After the MFMAs a lane holds, per 32x32 block (i,j) and q, 4
@@ -163,47 +250,60 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     // the XOR must map [0,NCH) onto itself: within aligned groups of 16 (NCH a multiple of 16) or 8
     auto stg_swz = [](int row) { return NCH % 16 == 0 ? (row & 15) : (NCH == 8 ? ((row >> 1) & 7) : (row & 7)); };
     const int rd_row0 = lane / LPR, rd_c = lane % LPR;
+    // The bias is fetched and WAITED FOR here, in code every lane runs.  If its first use
+    // sat in the row-guarded blocks below, the compiler could not tell at the next block
+    // whether the wait had happened and would wait for "all memory operations" again in
+    // every pass, which also waits for the previous pass's store: the passes would run
+    // one store round trip at a time.
+    const int n_ep = n0 + wn * TN + (rd_c < NCH ? rd_c : 0) * 4;
+    float4 bb = *reinterpret_cast<const float4*>(p.bias + n_ep);
+    asm volatile("" : "+v"(bb.x), "+v"(bb.y), "+v"(bb.z), "+v"(bb.w));
+    // Tiles that lie wholly inside M take the copy of the code without row guards, where the
+    // compiler is free to batch the LDS reads and stores of a slab.
+    auto emit = [&](auto guard_c) {
+        constexpr bool GUARD = decltype(guard_c)::value;
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
+        for (int i = 0; i < FM; ++i) {
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
+            for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = j * 8 + q * 2 + khalf;
-                *reinterpret_cast<float4*>(stg + l32 * TN + ((c ^ stg_swz(l32)) << 2)) =
-                    make_float4(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-            }
-        if (rd_c >= NCH) continue;                           // idle lanes of a row (uniform over i)
-        const int n = n0 + wn * TN + rd_c * 4;
-        const float4 bb = *reinterpret_cast<const float4*>(p.bias + n);
+                for (int q = 0; q < 4; ++q) {
+                    const int c = j * 8 + q * 2 + khalf;
+                    *reinterpret_cast<float4*>(stg + l32 * TN + ((c ^ stg_swz(l32)) << 2)) =
+                        make_float4(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                }
+            if (rd_c >= NCH) continue;                           // idle lanes of a row (uniform over i)
+            const int n = n_ep;
 #pragma unroll
-        for (int pass = 0; pass < 32 / RPP; ++pass) {
-            const int row = pass * RPP + rd_row0;
-            const float4 a4 = *reinterpret_cast<const float4*>(stg + row * TN + ((rd_c ^ stg_swz(row)) << 2));
-            const int64_t m = m0 + wm * TM + i * 32 + row;
-            if (m >= p.M) continue;
-            float v0 = a4.x + bb.x, v1 = a4.y + bb.y, v2 = a4.z + bb.z, v3 = a4.w + bb.w;
-            if (EPI == EPI_BIAS_SILU) { v0 = silu_fast(v0); v1 = silu_fast(v1); v2 = silu_fast(v2); v3 = silu_fast(v3); }
-            if (EPI == EPI_GATE_RES) {
-                const uint2 g = *reinterpret_cast<const uint2*>(p.gate + m * p.ldg + n);
-                float* cp = (float*)p.C + m * p.ldc + n;
-                const float4 c = *reinterpret_cast<const float4*>(cp);
-                v0 = fmaf(bf16_to_f32((bf16_t)(g.x & 0xFFFF)), v0, c.x);
-                v1 = fmaf(bf16_to_f32((bf16_t)(g.x >> 16)), v1, c.y);
-                v2 = fmaf(bf16_to_f32((bf16_t)(g.y & 0xFFFF)), v2, c.z);
-                v3 = fmaf(bf16_to_f32((bf16_t)(g.y >> 16)), v3, c.w);
-                *reinterpret_cast<float4*>(cp) = make_float4(v0, v1, v2, v3);
-            } else if (OUT_F32) {
-                *reinterpret_cast<float4*>((float*)p.C + m * p.ldc + n) = make_float4(v0, v1, v2, v3);
-            } else {
-                *reinterpret_cast<uint2*>((bf16_t*)p.C + m * p.ldc + n) =
-                    make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+            for (int pass = 0; pass < 32 / RPP; ++pass) {
+                const int row = pass * RPP + rd_row0;
+                const float4 a4 = *reinterpret_cast<const float4*>(stg + row * TN + ((rd_c ^ stg_swz(row)) << 2));
+                const int64_t m = m0 + wm * TM + i * 32 + row;
+                if (GUARD && m >= p.M) continue;
+                float v0 = a4.x + bb.x, v1 = a4.y + bb.y, v2 = a4.z + bb.z, v3 = a4.w + bb.w;
+                if (EPI == EPI_BIAS_SILU) { v0 = silu_fast(v0); v1 = silu_fast(v1); v2 = silu_fast(v2); v3 = silu_fast(v3); }
+                if (EPI == EPI_GATE_RES) {
+                    const uint2 g = *reinterpret_cast<const uint2*>(p.gate + m * p.ldg + n);
+                    float* cp = (float*)p.C + m * p.ldc + n;
+                    const float4 c = *reinterpret_cast<const float4*>(cp);
+                    v0 = fmaf(bf16_to_f32((bf16_t)(g.x & 0xFFFF)), v0, c.x);
+                    v1 = fmaf(bf16_to_f32((bf16_t)(g.x >> 16)), v1, c.y);
+                    v2 = fmaf(bf16_to_f32((bf16_t)(g.y & 0xFFFF)), v2, c.z);
+                    v3 = fmaf(bf16_to_f32((bf16_t)(g.y >> 16)), v3, c.w);
+                    *reinterpret_cast<float4*>(cp) = make_float4(v0, v1, v2, v3);
+                } else if (OUT_F32) {
+                    *reinterpret_cast<float4*>((float*)p.C + m * p.ldc + n) = make_float4(v0, v1, v2, v3);
+                } else {
+                    *reinterpret_cast<uint2*>((bf16_t*)p.C + m * p.ldc + n) =
+                        make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
+                }
             }
         }
-    }
+    };
+    if (m0 + BM <= p.M) emit(std::false_type{}); else emit(std::true_type{});
 }
 
-template <int BM, int BN, int WM, int WN, int BK, int NST>
+template <int BM, int BN, int WM, int WN, int BK, int NST, bool PIPE = false>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     Params p;
     p.A = (const bf16_t*)g.A; p.lda = g.lda; p.B = (const bf16_t*)g.B; p.bias = g.bias;
@@ -214,7 +314,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WM * WN * 64);
 #define CSD_LAUNCH(EPI, F32)                                                                                   \
     do {                                                                                                       \
-        auto kern = k_gemm_bf16<BM, BN, WM, WN, BK, NST, EPI, F32>;                                             \
+        auto kern = k_gemm_bf16<BM, BN, WM, WN, BK, NST, EPI, F32, PIPE>;                                            \
         static bool attr_done = false;                                                                          \
         if (!attr_done) {                                                                                       \
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
@@ -233,7 +333,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     return hipGetLastError();
 }
 
-// tuning hook: environment variable CSD_GEMM_VARIANT = 0..3 forces a tile shape
+// tuning hook: environment variable CSD_GEMM_VARIANT = 0..9 forces a tile shape / main loop
 int gemm_variant_override() {
     static int v = -2;
     if (v == -2) { const char* e = getenv("CSD_GEMM_VARIANT"); v = (e && *e) ? atoi(e) : -1; }
@@ -252,13 +352,13 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
         // large problems: 256-row tiles, 256 (or 192) columns wide
         // (192 wins for one GEMM alone on the chip, e.g. 16384x768x768: 28 vs 34 us, but loses 5 % on
         // the whole path, where several chains share the chip; it is used only where 256 does not divide N)
-        if (g.M >= 2048 && g.N % 256 == 0) variant = 1;
+        if (g.M >= 2048 && g.N % 256 == 0) variant = 9;
         else if (g.M >= 2048 && g.N % 192 == 0) variant = 8;
         else variant = (g.N % 128 == 0 && g.M >= 256) ? 2 : 3;
     }
-    if ((variant == 0 || variant == 1) && g.N % 256 != 0) variant = (g.N % 192 == 0 && g.M >= 2048) ? 8 : 3;
+    if ((variant == 0 || variant == 1 || variant == 9) && g.N % 256 != 0) variant = (g.N % 192 == 0 && g.M >= 2048) ? 8 : 3;
     if (variant == 8 && g.N % 192 != 0) variant = 3;
-    if ((variant == 2 || (variant >= 4 && variant != 8)) && g.N % 128 != 0) variant = 3;
+    if ((variant == 2 || (variant >= 4 && variant < 8)) && g.N % 128 != 0) variant = 3;
     if (variant == 7) {
         static int safe = -1;
         if (safe < 0) { const char* e = getenv("CSD_GEMM_SAFE_WAIT"); safe = (e && *e == '1') ? 1 : 0; }
@@ -272,6 +372,8 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
         case 4: return launch_cfg<256, 128, 2, 2, 32, 3>(g, st);    // 4 waves, 128x64 per wave, 72 KiB LDS: 2 per CU
         case 5: return launch_cfg<256, 128, 2, 2, 32, 2>(g, st);    // same, 48 KiB LDS
         case 6: return launch_cfg<256, 128, 2, 2, 64, 2>(g, st);    // same tile, BK 64, 96 KiB LDS
+        case 9: if (g.K >= 256) return launch_cfg<256, 256, 2, 4, 64, 2, true>(g, st);   // 8 waves, software-pipelined main loop
+                return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);
         case 8: return launch_cfg<256, 192, 4, 2, 64, 2>(g, st);    // 8 waves, 64x96 per wave: N = 3 * 2^k widths
         default: return launch_cfg<64, 64, 2, 2, 64, 2>(g, st);     // 4 waves, 32x32 per wave
     }
