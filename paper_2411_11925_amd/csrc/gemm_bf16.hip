@@ -359,12 +359,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
     if ((variant == 0 || variant == 1 || variant == 9) && g.N % 256 != 0) variant = (g.N % 192 == 0 && g.M >= 2048) ? 8 : 3;
     if (variant == 8 && g.N % 192 != 0) variant = 3;
     if ((variant == 2 || (variant >= 4 && variant < 8)) && g.N % 128 != 0) variant = 3;
-    if (variant == 7) {
-        static int safe = -1;
-        if (safe < 0) { const char* e = getenv("CSD_GEMM_SAFE_WAIT"); safe = (e && *e == '1') ? 1 : 0; }
-        if (g.N % 256 == 0 && !g.c_is_f32 && g.epi != EPI_GATE_RES) return launch_gemm_bf16_persist(g, st, safe);
-        variant = (g.N % 256 == 0) ? 1 : (g.N % 128 == 0 ? 2 : 3);
-    }
+    if (variant == 7) variant = 9;
     switch (variant) {
         case 0: return launch_cfg<256, 256, 2, 2, 64, 2>(g, st);    // 4 waves, 128x128 per wave, 128 KiB LDS
         case 1: return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);    // 8 waves, 128x64 per wave, 128 KiB LDS

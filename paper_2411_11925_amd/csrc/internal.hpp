@@ -88,8 +88,6 @@ struct GemmArgs {
 
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st);
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st);
-// persistent variant for bf16 outputs with N % 256 == 0 (bias / bias+SiLU epilogues)
-hipError_t launch_gemm_bf16_persist(const GemmArgs& g, hipStream_t st, int safe_wait);
 
 // s = silu(E_t + e)
 hipError_t launch_cond_silu(const float* e, const float* time_emb_t, void* s, int act, int64_t R, int W, hipStream_t st);

@@ -228,7 +228,10 @@ def _bf16(a):
 
 
 @pytest.mark.parametrize("M,N,K", [(1, 64, 64), (70, 128, 192), (300, 192, 128), (515, 256, 1024),
-                                   (2048 + 37, 768, 256), (4096, 1024, 1024)])
+                                   (2048 + 37, 768, 256), (4096, 1024, 1024),
+                                   # more tiles than CUs (several tiles per persistent workgroup), ragged
+                                   # last row of tiles, tile counts that do and do not divide by 8
+                                   (8192 + 100, 3072, 512), (16384, 2304, 192)])
 def test_gemm_bf16_all_epilogues(B, M, N, K):
     rng = np.random.default_rng(M + N + K)
     A = S.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
@@ -244,6 +247,8 @@ def test_gemm_bf16_all_epilogues(B, M, N, K):
     assert np.max(np.abs(out - ref) / (1 + np.abs(ref))) < 5e-3          # bf16 store
     out = B.csd_gemm_bf16(_bf16(A), _bf16(W), _t(bias), 1, out_f32=True).cpu().numpy()
     assert np.max(np.abs(out - O.silu(ref))) < tol
+    out = B.csd_gemm_bf16(_bf16(A), _bf16(W), _t(bias), 1).float().cpu().numpy()
+    assert np.max(np.abs(out - O.silu(ref)) / (1 + np.abs(ref))) < 5e-3  # bf16 store
     h = _t(h0.copy())
     B.csd_gemm_bf16(_bf16(A), _bf16(W), _t(bias), 2, C=h, gate=_bf16(gate))
     assert np.max(np.abs(h.cpu().numpy() - (h0 + gate.astype(np.float64) * ref))) < tol * 4
