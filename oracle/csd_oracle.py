@@ -46,6 +46,7 @@ STREAM_TRAJ = 0      # slot T is x_T, slot t-1 is eps_t for t = T..1
 STREAM_ACCEPT_U = 1  # slot 0: the uniform r_i of the accept test
 STREAM_RESAMPLE_N = 2  # slot k: proposal noise of resampling trial k
 STREAM_RESAMPLE_U = 3  # slot k: uniform of resampling trial k
+STREAM_BONUS = 4     # trajectory noise of the target-only sample x ~ p_{gamma+1}, keyed by the global GROUP index
 
 
 # --------------------------------------------------------------------------
@@ -423,6 +424,84 @@ def denoise_lockstep(draft: Head, target: Head, z_q, z_p, seed: int,
                 extras["trace"] = trace
             return summary, extras
     raise AssertionError("T must be >= 1")
+
+
+# --------------------------------------------------------------------------
+# Split-phase form of Alg. 1: the draft head position by position as the draft
+# AR model advances, then the target head on all positions at once
+# --------------------------------------------------------------------------
+def head_trajectory(head: Head, z, global_rows, seed: int, tau: float = 1.0,
+                    stream: int = STREAM_TRAJ):
+    """One head alone from x_T = eps_T to x_0 for the rows `global_rows` (the
+    counters that key the noise).  Returns mu_1, logvar_1, x_0 and
+    1/2 sum_{t=2..T} sum_d log sigma^2_{t,d} (this head's half of Eq. 6)."""
+    D, T = head.cfg.token_dim, head.cfg.n_steps
+    z = np.asarray(z, dtype=np.float64)
+    rows = np.asarray(global_rows, dtype=np.uint64)
+    e = head.cond_embed(z)
+    x = normals(seed, rows, T, stream, D)
+    half = np.zeros(z.shape[0])
+    for t in range(T, 0, -1):
+        eh, v = head.forward(x, t, e)
+        mu, lv = transition_params(head.sched, x, t, eh, v)
+        xn = mu + tau * np.exp(0.5 * lv) * normals(seed, rows, t - 1, stream, D)
+        if t >= 2:
+            half += 0.5 * np.sum(lv, axis=-1)
+            x = xn
+        else:
+            return dict(mu1=mu, lv1=lv, x0=xn, half_logvar=half)
+    raise AssertionError("T must be >= 1")
+
+
+def denoise_draft(draft: Head, z_q_pos, gamma: int, position: int, seed: int,
+                  row_offset: int, tau: float, summary: np.ndarray):
+    """Draft phase for ONE position (0-based) of every group (Alg. 1, the loop
+    "for i = 1..gamma: x_i ~ q_i").  z_q_pos: [G, C].  Fills, in the rows
+    g*gamma + position of `summary` ([G*gamma, 5D+1], in place): mu^q_1,
+    logvar^q_1, the draft token x_0, and the draft's half of log Sigma in the
+    last column.  Noise counters are the same global rows as in the lockstep form."""
+    D = draft.cfg.token_dim
+    G = np.asarray(z_q_pos).shape[0]
+    local = np.arange(G, dtype=np.int64) * gamma + position
+    tr = head_trajectory(draft, z_q_pos, row_offset + local.astype(np.uint64), seed, tau)
+    summary[local, 2 * D:3 * D] = tr["mu1"]
+    summary[local, 3 * D:4 * D] = tr["lv1"]
+    summary[local, 4 * D:5 * D] = tr["x0"]
+    summary[local, 5 * D] = tr["half_logvar"]
+    return tr["x0"]
+
+
+def denoise_target(target: Head, z_p, seed: int, row_offset: int, tau: float,
+                   summary: np.ndarray):
+    """Target phase for all R = G*gamma rows at once (Alg. 1, "compute
+    p_1..p_gamma in parallel", with the draft's eps_t regenerated from the
+    counters).  z_p: [R, C].  Fills mu^p_1, logvar^p_1 and turns the last
+    column into log Sigma = (draft half) - (target half)  (Eq. 6)."""
+    D = target.cfg.token_dim
+    R = np.asarray(z_p).shape[0]
+    tr = head_trajectory(target, z_p, row_offset + np.arange(R, dtype=np.uint64), seed, tau)
+    summary[:, 0:D] = tr["mu1"]
+    summary[:, D:2 * D] = tr["lv1"]
+    summary[:, 5 * D] = summary[:, 5 * D] - tr["half_logvar"]
+
+
+def sample(head: Head, z, seed: int, row_offset: int = 0, tau: float = 1.0,
+           stream: int = STREAM_TRAJ):
+    """Plain sampling x_0 ~ head(.|z) for rows row_offset.. (target-only mode:
+    pre-filling, and the token from p_{gamma+1} that Alg. 1 returns when all
+    gamma drafts are accepted; that one uses STREAM_BONUS and group indices)."""
+    R = np.asarray(z).shape[0]
+    return head_trajectory(head, z, row_offset + np.arange(R, dtype=np.uint64), seed, tau, stream)["x0"]
+
+
+def append_bonus(tokens, n_out, n_accept, bonus, gamma: int):
+    """Groups whose gamma drafts were all accepted also emit the target's own
+    sample for position gamma+1 (Alg. 1, last line).  In place; returns n_out."""
+    tokens = np.asarray(tokens); n_out = np.asarray(n_out)
+    full = np.asarray(n_accept) == gamma
+    tokens[full, gamma, :] = np.asarray(bonus)[full]
+    n_out[full] = gamma + 1
+    return n_out
 
 
 def split_summary(summary, D: int):

@@ -479,3 +479,87 @@ def test_tiny_workload_runs_and_is_deterministic():
     assert np.array_equal(a[64:], b)           # rows are independent and keyed globally
     _, _, mask, _ = O.verify(a, 64, 2, wl.seed)
     assert 0.2 < mask.mean() < 0.8
+
+
+# ------------------------------------------- split-phase form and the bonus token
+def test_split_phase_equals_lockstep():
+    """Alg. 1 run the way an AR loop runs it - the draft head one position at a time, then
+    the target head on all positions, each regenerating eps_t from the counters - must give
+    the lockstep summary: same trajectories, same log Sigma (two separately written loops)."""
+    shape, cfg, dq, tp = _tiny_pair(T=6)
+    G, gamma, D = 4, 3, cfg.token_dim
+    zq, zp = S.cond_vectors(G * gamma, cfg.cond_dim, 5, add_std=0.3)
+    ref, _ = O.denoise_lockstep(dq, tp, zq, zp, seed=11, row_offset=640, tau=0.8)
+    summ = np.full((G * gamma, 5 * D + 1), np.nan)
+    for i in range(gamma):
+        x_i = O.denoise_draft(dq, zq.reshape(G, gamma, -1)[:, i], gamma, i, 11, 640, 0.8, summ)
+        assert np.array_equal(x_i, summ[i::gamma, 4 * D:5 * D])
+    O.denoise_target(tp, zp, 11, 640, 0.8, summ)
+    assert np.allclose(summ, ref, rtol=1e-12, atol=1e-12)
+    # a draft phase with the wrong position index shifts the noise rows and must NOT match
+    bad = np.zeros_like(summ)
+    O.denoise_draft(dq, zq.reshape(G, gamma, -1)[:, 0], gamma, 1, 11, 640, 0.8, bad)
+    assert not np.allclose(bad[1::gamma, 4 * D:5 * D], ref[0::gamma, 4 * D:5 * D])
+
+
+def test_sample_zero_output_layer_closed_form_and_bonus_stream():
+    """Target-only sampling with a zero output layer is the same linear function of its
+    noise slots as in the lockstep pin, now on the bonus stream; that stream is not the
+    trajectory stream (other values, uncorrelated)."""
+    shape = S.HeadShape(8, 6, 16, 2)
+    blob = S.head_weights(shape, 3, bias_std=0.1)
+    _set(blob, shape, "out.w", 0.0)
+    _set(blob, shape, "out.b", 0.0)
+    h = O.Head(O.HeadCfg(8, 6, 16, 2, 8, eps_skip_gain=0.5), blob)
+    z, _ = S.cond_vectors(7, 6, 2, add_std=1.0)
+    seed, off, tau = 5, 300, 1.1
+    got = O.sample(h, z, seed, off, tau, O.STREAM_BONUS)
+    s = h.sched
+    rows = off + np.arange(7, dtype=np.uint64)
+    x = O.normals(seed, rows, 8, O.STREAM_BONUS, 8)
+    for t in range(8, 0, -1):
+        a = (1 - 0.5 * s.beta[t]) / math.sqrt(s.alpha[t])
+        sig = math.exp(0.25 * (s.log_beta[t] + s.log_beta_tilde_clip[t]))
+        x = a * x + tau * sig * O.normals(seed, rows, t - 1, O.STREAM_BONUS, 8)
+    assert np.allclose(got, x, rtol=1e-12)
+    assert not np.allclose(got, O.sample(h, z, seed, off, tau, O.STREAM_TRAJ))
+    big = np.arange(20000, dtype=np.uint64)
+    a, b = O.normals(9, big, 3, O.STREAM_BONUS, 4), O.normals(9, big, 3, O.STREAM_TRAJ, 4)
+    assert abs(np.corrcoef(a.ravel(), b.ravel())[0, 1]) < 0.02
+    assert abs(a.mean()) < 0.02 and abs(a.std() - 1) < 0.02
+
+
+def test_sample_reproduces_the_head_distribution_in_one_dimension():
+    """With a zero output layer the head is a fixed linear Gaussian chain, so x_0 is
+    N(0, v) with v in closed form; the sampler's empirical variance must match."""
+    shape = S.HeadShape(4, 8, 16, 1)
+    blob = S.head_weights(shape, 4)
+    _set(blob, shape, "out.w", 0.0)
+    _set(blob, shape, "out.b", 0.0)
+    T = 5
+    h = O.Head(O.HeadCfg(4, 8, 16, 1, T, eps_skip_gain=1.0), blob)
+    z, _ = S.cond_vectors(4000, 8, 3, add_std=0.0)
+    x0 = O.sample(h, z, 123, 0, 1.0, O.STREAM_BONUS)
+    s = h.sched
+    var = 1.0
+    for t in range(T, 0, -1):
+        a = (1 - s.beta[t]) / math.sqrt(s.alpha[t])
+        var = a * a * var + math.exp(0.5 * (s.log_beta[t] + s.log_beta_tilde_clip[t]))
+    assert abs(x0.var() / var - 1) < 0.05
+    assert abs(x0.mean()) < 4 * math.sqrt(var / x0.size)
+
+
+def test_append_bonus_only_for_fully_accepted_groups():
+    gamma, D = 3, 2
+    tokens = np.arange(4 * (gamma + 1) * D, dtype=np.float64).reshape(4, gamma + 1, D)
+    before = tokens.copy()
+    n_accept = np.array([3, 0, 2, 3])
+    n_out = np.array([3, 1, 3, 3])
+    bonus = -np.ones((4, D)) * np.arange(1, 5)[:, None]
+    out = O.append_bonus(tokens, n_out, n_accept, bonus, gamma)
+    assert list(out) == [4, 1, 3, 4]
+    for g in range(4):
+        if n_accept[g] == gamma:
+            assert np.array_equal(tokens[g, gamma], bonus[g]) and np.array_equal(tokens[g, :gamma], before[g, :gamma])
+        else:
+            assert np.array_equal(tokens[g], before[g])
