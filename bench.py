@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--dtype", default=None, choices=[None, "bf16", "f32"])
     ap.add_argument("--rows", type=int, default=0, help="rows per step (default: the whole workload)")
     ap.add_argument("--oracle-rows", type=int, default=128, help="rows of the CPU-oracle sample (0: skip)")
+    ap.add_argument("--no-latency-shape", action="store_true", help="skip the split-phase latency-shape figure")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 256 MiB device to device once (a kernel of known "
                          "traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -168,6 +169,40 @@ def main():
                                                                  "note": "same kernel and shapes, no other chain running"},
                      "traffic": measured_traffic(wl.name, dtype, R)},
     }
+
+    # Secondary figure: one verify window the way an autoregressive loop runs Alg. 1 (split-phase
+    # calls at the per-step shape: gamma draft calls of `batch` rows, one target call of batch*gamma
+    # rows, accept test, resampling, bonus token).  Launch-latency bound; reported, not the metric.
+    if not a.no_latency_shape:
+        Gl = wl.batch
+        Rl = Gl * gamma
+        zq3 = z_q[:Rl].reshape(Gl, gamma, -1)
+        zq_pos = [zq3[:, i].contiguous() for i in range(gamma)]
+        zb = z_p[:Gl].contiguous()                  # stands in for the cond vectors of position gamma+1
+        summ_l = torch.empty((Rl, 5 * D + 1), dtype=torch.float32, device=dev)
+
+        def window():
+            for i in range(gamma):
+                B.csd_denoise_draft(h_q, zq_pos[i], Gl, gamma, i, wl.seed, 0, 1.0, summ_l, ws)
+            B.csd_denoise_target(h_p, h_q, z_p[:Rl], Gl, gamma, wl.seed, 0, 1.0, summ_l, ws)
+            na, _, _ = B.csd_verify(summ_l, Gl, gamma, D, wl.seed, want_log_ratio=False, want_mask=False)
+            tok, no, _, _ = B.csd_resample(summ_l, na, Gl, gamma, D, wl.seed)
+            bonus = B.csd_sample(h_p, zb, wl.seed, 0, B.CSD_STREAM_BONUS, 1.0, workspace=ws)
+            B.csd_append_bonus(tok, no, na, bonus, gamma)
+            return no
+        window(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 3
+        e0.record()
+        for _ in range(reps):
+            n_emit = window()
+        e1.record(); torch.cuda.synchronize()
+        ms_w = e0.elapsed_time(e1) / reps
+        res["latency_shape"] = {"what": "one verify window, split-phase calls: %d draft calls of %d rows, one target "
+                                        "call of %d rows, verify, resample, bonus sample of %d rows" % (gamma, Gl, Rl, Gl),
+                                "ms_per_window": ms_w, "verified_tokens_per_s": Rl / (ms_w / 1e3),
+                                "emitted_tokens_per_s": float(n_emit.sum().item()) / (ms_w / 1e3),
+                                "head_passes": (gamma + 2) * wl.n_steps}
 
     if a.oracle_rows > 0:
         from oracle import csd_oracle as O

@@ -55,6 +55,8 @@ extern "C" {
 #define CSD_STREAM_ACCEPT_U    1  /* slot 0: the uniform r_i of the accept test */
 #define CSD_STREAM_RESAMPLE_N  2  /* slot k: proposal noise of resampling trial k */
 #define CSD_STREAM_RESAMPLE_U  3  /* slot k: uniform of resampling trial k */
+#define CSD_STREAM_BONUS       4  /* trajectory noise of the target-only sample for position gamma+1;
+                                    its "row" is the global GROUP index */
 
 /* bits of flags[g] written by csd_resample */
 #define CSD_FLAG_CAP        1u    /* max_trips reached; the last proposal was emitted */
@@ -144,6 +146,51 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target,
                          void* hip_stream);
 
 /*
+ * Split-phase form of the same computation, the way an autoregressive loop runs
+ * Alg. 1: the draft head is called once per position as the draft AR model
+ * advances ("for i = 1..gamma: x_i ~ q_i"), then the target head once on all
+ * positions ("compute p_1..p_gamma in parallel"); the target regenerates the
+ * draft's eps_t from the counters (Sec. 3.2), nothing but the summary is kept
+ * between the calls.
+ *
+ * csd_denoise_draft: position (0-based) `position` of every group.  z_q: device
+ * [G, C] (one conditioning vector per group).  Fills, in rows g*gamma+position
+ * of `summary` (device [G*gamma, 5D+1], the other rows and columns untouched):
+ * mu^q_1, log sigma^2_{q,1}, the draft token x_0 (columns [4D,5D): what the
+ * draft AR model consumes next) and, in the last column, the draft's half of
+ * log Sigma.  Noise counters are the lockstep call's: global row
+ * row_offset + g*gamma + position.  Workspace: csd_workspace_bytes(draft,NULL,G).
+ *
+ * csd_denoise_target: all R = G*gamma rows.  z_p: device [R, C].  Fills mu^p_1,
+ * log sigma^2_{p,1} and turns the last column into log Sigma (Eq. 6).  `draft`
+ * is consulted for its schedule only.  After both phases the summary holds
+ * bit for bit what csd_denoise_lockstep writes.  Workspace:
+ * csd_workspace_bytes(NULL,target,R).
+ * Errors as csd_denoise_lockstep.
+ */
+int csd_denoise_draft(const csd_head_t* draft, const float* z_q,
+                      int64_t n_groups, int32_t gamma, int32_t position,
+                      uint64_t seed, uint64_t row_offset, float temperature,
+                      float* summary, void* workspace, size_t workspace_bytes, void* hip_stream);
+int csd_denoise_target(const csd_head_t* target, const csd_head_t* draft, const float* z_p,
+                       int64_t n_groups, int32_t gamma,
+                       uint64_t seed, uint64_t row_offset, float temperature,
+                       float* summary, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Plain sampling from one head (target-only mode): x_0 ~ head(.|z) by the same
+ * T-step reverse process (Sec. 3.1, Eq. 3), no verification.  Serves pre-filling
+ * (Sec. 3.4) and the token from p_{gamma+1} that Alg. 1 returns when all gamma
+ * drafts are accepted; for that one pass rng_stream = CSD_STREAM_BONUS and
+ * row_offset = the global index of the first group, so its noise is independent
+ * of every draft trajectory.  z: device [n_rows, C]; tokens: device [n_rows, D].
+ * Workspace: csd_workspace_bytes(head,NULL,n_rows).
+ */
+int csd_sample(const csd_head_t* head, const float* z, int64_t n_rows,
+               uint64_t seed, uint64_t row_offset, int32_t rng_stream, float temperature,
+               float* tokens, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Accept test and first-reject scan (Alg. 1; Eq. 7).  Per row
  *   log_ratio = log Sigma + log N(x_0; mu^p_1, (temperature*sigma_{p,1})^2)
  *                         - log N(x_0; mu^q_1, (temperature*sigma_{q,1})^2),
@@ -173,6 +220,16 @@ int csd_resample(const float* summary, const int32_t* n_accept,
                  uint64_t seed, uint64_t row_offset, float temperature, int32_t max_trips,
                  float* tokens, int32_t* n_out, int32_t* trips, uint32_t* flags,
                  void* hip_stream);
+
+/*
+ * Alg. 1, last line: a group whose gamma drafts were all accepted also emits the
+ * target's own sample for position gamma+1.  For every g with n_accept[g] ==
+ * gamma: tokens[g, gamma, :] = bonus[g, :] and n_out[g] = gamma+1; other groups
+ * are untouched.  tokens [G,gamma+1,D], n_out [G], n_accept [G], bonus [G,D]:
+ * device; run after csd_resample on the same stream.
+ */
+int csd_append_bonus(float* tokens, int32_t* n_out, const int32_t* n_accept, const float* bonus,
+                     int64_t n_groups, int32_t gamma, int32_t token_dim, void* hip_stream);
 
 /*
  * Stage-wise access for tests and profiling: one head evaluation

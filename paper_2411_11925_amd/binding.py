@@ -26,10 +26,12 @@ CSD_OK, CSD_EINVAL, CSD_ENOMEM, CSD_EHIP, CSD_EUNSUPPORTED = 0, -1, -2, -3, -4
 CSD_F32, CSD_BF16 = 0, 1
 CSD_COSINE, CSD_TABLE = 0, 1
 CSD_STREAM_TRAJ, CSD_STREAM_ACCEPT_U, CSD_STREAM_RESAMPLE_N, CSD_STREAM_RESAMPLE_U = 0, 1, 2, 3
+CSD_STREAM_BONUS = 4
 CSD_FLAG_CAP, CSD_FLAG_NONFINITE = 1, 2
 
 EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_workspace_bytes",
-           "csd_denoise_lockstep", "csd_verify", "csd_resample", "csd_head_eval",
+           "csd_denoise_lockstep", "csd_denoise_draft", "csd_denoise_target", "csd_sample",
+           "csd_verify", "csd_resample", "csd_append_bonus", "csd_head_eval",
            "csd_rng_normals", "csd_rng_uniforms", "csd_gemm_bf16", "csd_profile_enable", "csd_profile_read", "csd_last_error"]
 
 
@@ -54,6 +56,17 @@ _lib.csd_workspace_bytes.argtypes = [c_void_p, c_void_p, c_int64]
 _lib.csd_denoise_lockstep.restype = c_int
 _lib.csd_denoise_lockstep.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_uint64,
                                       c_uint64, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.csd_denoise_draft.restype = c_int
+_lib.csd_denoise_draft.argtypes = [c_void_p, c_void_p, c_int64, c_int32, c_int32, c_uint64, c_uint64, c_float,
+                                   c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.csd_denoise_target.restype = c_int
+_lib.csd_denoise_target.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_uint64, c_uint64, c_float,
+                                    c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.csd_sample.restype = c_int
+_lib.csd_sample.argtypes = [c_void_p, c_void_p, c_int64, c_uint64, c_uint64, c_int32, c_float, c_void_p, c_void_p,
+                            c_size_t, c_void_p]
+_lib.csd_append_bonus.restype = c_int
+_lib.csd_append_bonus.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_void_p]
 _lib.csd_verify.restype = c_int
 _lib.csd_verify.argtypes = [c_void_p, c_int64, c_int32, c_int32, c_uint64, c_uint64, c_float,
                             c_void_p, c_void_p, c_void_p, c_void_p]
@@ -176,6 +189,62 @@ def csd_denoise_lockstep(draft: Head, target: Head, z_q: torch.Tensor, z_p: torc
                                      seed, row_offset, temperature, _ptr(summary), _ptr(workspace),
                                      workspace.numel(), _stream(stream)))
     return summary
+
+
+def csd_denoise_draft(draft: Head, z_q: torch.Tensor, n_groups: int, gamma: int, position: int, seed: int,
+                      row_offset: int, temperature: float, summary: torch.Tensor,
+                      workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    D = draft.cfg.token_dim
+    assert z_q.is_cuda and z_q.dtype == torch.float32 and z_q.is_contiguous()
+    assert tuple(z_q.shape) == (n_groups, draft.cfg.cond_dim)
+    assert summary.is_cuda and summary.is_contiguous() and summary.dtype == torch.float32
+    assert tuple(summary.shape) == (n_groups * gamma, 5 * D + 1)
+    if workspace is None:
+        workspace, _ = _workspace(draft, None, n_groups, z_q.device)
+    _check(_lib.csd_denoise_draft(draft.handle, _ptr(z_q), n_groups, gamma, position, seed, row_offset, temperature,
+                                  _ptr(summary), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return summary
+
+
+def csd_denoise_target(target: Head, draft: Head, z_p: torch.Tensor, n_groups: int, gamma: int, seed: int,
+                       row_offset: int, temperature: float, summary: torch.Tensor,
+                       workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    R, D = n_groups * gamma, target.cfg.token_dim
+    assert z_p.is_cuda and z_p.dtype == torch.float32 and z_p.is_contiguous()
+    assert tuple(z_p.shape) == (R, target.cfg.cond_dim)
+    assert summary.is_cuda and summary.is_contiguous() and summary.dtype == torch.float32
+    assert tuple(summary.shape) == (R, 5 * D + 1)
+    if workspace is None:
+        workspace, _ = _workspace(None, target, R, z_p.device)
+    _check(_lib.csd_denoise_target(target.handle, draft.handle, _ptr(z_p), n_groups, gamma, seed, row_offset,
+                                   temperature, _ptr(summary), _ptr(workspace), workspace.numel(), _stream(stream)))
+    return summary
+
+
+def csd_sample(head: Head, z: torch.Tensor, seed: int, row_offset: int = 0, rng_stream: int = CSD_STREAM_TRAJ,
+               temperature: float = 1.0, tokens: torch.Tensor | None = None,
+               workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    n, D = z.shape[0], head.cfg.token_dim
+    assert z.is_cuda and z.dtype == torch.float32 and z.is_contiguous() and z.shape[1] == head.cfg.cond_dim
+    if tokens is None:
+        tokens = torch.empty((n, D), dtype=torch.float32, device=z.device)
+    assert tokens.is_cuda and tokens.is_contiguous() and tokens.dtype == torch.float32 and tuple(tokens.shape) == (n, D)
+    if workspace is None:
+        workspace, _ = _workspace(head, None, n, z.device)
+    _check(_lib.csd_sample(head.handle, _ptr(z), n, seed, row_offset, rng_stream, temperature, _ptr(tokens),
+                           _ptr(workspace), workspace.numel(), _stream(stream)))
+    return tokens
+
+
+def csd_append_bonus(tokens: torch.Tensor, n_out: torch.Tensor, n_accept: torch.Tensor, bonus: torch.Tensor,
+                     gamma: int, stream=None):
+    G, D = n_accept.numel(), bonus.shape[1]
+    assert tokens.is_cuda and tokens.is_contiguous() and tokens.dtype == torch.float32
+    assert tuple(tokens.shape) == (G, gamma + 1, D) and tuple(bonus.shape) == (G, D)
+    assert bonus.is_cuda and bonus.is_contiguous() and bonus.dtype == torch.float32
+    assert n_out.dtype == torch.int32 and n_accept.dtype == torch.int32 and n_out.numel() == G
+    _check(_lib.csd_append_bonus(_ptr(tokens), _ptr(n_out), _ptr(n_accept), _ptr(bonus), G, gamma, D, _stream(stream)))
+    return tokens, n_out
 
 
 def csd_verify(summary: torch.Tensor, n_groups: int, gamma: int, token_dim: int, seed: int,

@@ -196,6 +196,7 @@ TransArgs trans_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
     TransArgs f{};
     f.o = ws.o; f.ldo = 64; f.R = R; f.D = hd->D; f.x = ws.x; f.acc = ws.acc;
     f.coef = hd->coef[t]; f.t = t;
+    f.row_stride = 1; f.row_shift = 0; f.rng_stream = CSD_STREAM_TRAJ;
     return f;
 }
 
@@ -238,6 +239,98 @@ struct DeviceGuard {
     explicit DeviceGuard(int dev) { if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess) ok = true; }
     ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
 };
+
+
+// One chain = one head walking rows [0, n) of its slice from x_T to x_0 on its own stream.
+// Row r of the chain is row r*row_stride + row_shift of the slice's summary and, behind
+// row_offset, of the noise counters.
+struct Chain {
+    const csd_head* hd; HeadWs ws; const float* z; int64_t n;
+    uint64_t row_offset; int64_t row_stride, row_shift; int rng_stream;
+    float* summary; int is_target; float* tokens;
+    hipStream_t s;
+};
+
+// Cuts n rows into row chunks (multiples of 256 rows, so every result is bit-identical to a
+// single-chain run): 2 for >= 8192 rows unless CSD_ROW_CHUNKS says otherwise.
+int plan_chunks(int64_t n, bool have_side, int64_t* chunk_rows) {
+    int n_chunks = row_chunks_setting();
+    if (n_chunks == 0) n_chunks = (n >= 8192) ? 2 : 1;
+    if (!have_side) n_chunks = 1;
+    int64_t rows = ((n + n_chunks - 1) / n_chunks + 255) / 256 * 256;
+    if (rows >= n) { n_chunks = 1; rows = n; }
+    *chunk_rows = rows;
+    return (int)((n + rows - 1) / rows);
+}
+
+// Runs the chains to the end.  Chain 0 uses the caller's stream, the others side streams of
+// default priority; fork and join are events on the caller's stream, the host is never
+// synchronised.  The chains run free: one chain's memory-bound kernels and GEMM epilogues fill
+// the gaps of another chain's MFMA loops.  (Tying them into a fixed GEMM/row-kernel pipeline
+// with events was measured and is slower: every cross-stream hand-over costs more than the
+// overlap it buys.)
+int run_chains(Chain* chains, int n_chains, uint64_t seed, float tau, hipStream_t st, SideStreams* side) {
+    for (int i = 0; i < n_chains; ++i) chains[i].s = (i == 0 || !side) ? st : side->stream[i - 1];
+    if (side && n_chains > 1) {
+        HIP_TRY(hipEventRecord(side->fork, st));
+        for (int i = 1; i < n_chains; ++i) HIP_TRY(hipStreamWaitEvent(chains[i].s, side->fork, 0));
+    }
+    const int T = chains[0].hd->T;
+    for (int i = 0; i < n_chains; ++i) {
+        Chain& ch = chains[i];
+        HIP_TRY(launch_init_x(ch.ws.x, ch.ws.acc, ch.n, ch.hd->D, T, seed, ch.row_offset, ch.row_stride, ch.row_shift,
+                              ch.rng_stream, ch.s));
+        HIP_TRY(cond_embed(ch.hd, ch.z, ch.ws, ch.n, ch.s));
+    }
+    for (int t = T; t >= 1; --t) {
+        for (int i = 0; i < n_chains; ++i) {
+            Chain& ch = chains[i];
+            HIP_TRY(head_body(ch.hd, ch.ws, t, ch.n, ch.s));
+            TransArgs f = trans_args(ch.hd, ch.ws, t, ch.n);
+            f.seed = seed; f.row_offset = ch.row_offset; f.tau = tau;
+            f.row_stride = ch.row_stride; f.row_shift = ch.row_shift; f.rng_stream = ch.rng_stream;
+            f.summary = ch.summary; f.is_target = ch.is_target; f.tokens = ch.tokens;
+            HIP_TRY(launch_transition(f, ch.s));
+        }
+    }
+    if (side && n_chains > 1) {
+        for (int i = 1; i < n_chains; ++i) {
+            HIP_TRY(hipEventRecord(side->join[i], chains[i].s));
+            HIP_TRY(hipStreamWaitEvent(st, side->join[i], 0));
+        }
+    }
+    return CSD_OK;
+}
+
+// argument checks shared by the denoising entry points
+int check_ws(const char* who, const void* workspace, size_t have, size_t need) {
+    if (!workspace) return fail(CSD_EINVAL, "%s: NULL buffer", who);
+    if (((uintptr_t)workspace & 255u) != 0) return fail(CSD_EINVAL, "%s: workspace must be 256-byte aligned", who);
+    if (have < need) return fail(CSD_EINVAL, "%s: workspace of %zu bytes, need %zu", who, have, need);
+    return CSD_OK;
+}
+
+// One head alone over n contiguous local rows (chunked into chains).
+int run_single_head(const csd_head* hd, const float* z, int64_t n, uint64_t seed, uint64_t row_offset,
+                    int64_t row_stride, int64_t row_shift, int rng_stream, float tau, float* summary, int is_target,
+                    float* tokens, void* workspace, hipStream_t st, Chain* chains, int* n_chains_out) {
+    SideStreams* side = side_streams(hd->device);
+    int64_t chunk_rows;
+    const int n_chunks = plan_chunks(n, side != nullptr, &chunk_rows);
+    char* wp = (char*)workspace;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t r0 = c * chunk_rows, m = (n - r0 < chunk_rows) ? n - r0 : chunk_rows;
+        Chain& ch = chains[c];
+        ch.hd = hd; ch.n = m; ch.z = z + r0 * hd->C;
+        ch.row_offset = row_offset + (uint64_t)(r0 * row_stride); ch.row_stride = row_stride; ch.row_shift = row_shift;
+        ch.rng_stream = rng_stream; ch.is_target = is_target;
+        ch.summary = summary ? summary + r0 * row_stride * (5 * hd->D + 1) : nullptr;
+        ch.tokens = tokens ? tokens + r0 * hd->D : nullptr;
+        wp = carve(hd, m, wp, &ch.ws);
+    }
+    *n_chains_out = n_chunks;
+    return run_chains(chains, n_chunks, seed, tau, st, side);
+}
 
 }  // namespace
 
@@ -442,75 +535,111 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, cons
         return fail(CSD_EINVAL, "csd_denoise_lockstep: workspace of %zu bytes, need %zu", workspace_bytes,
                     csd_workspace_bytes(draft, target, R));
     hipStream_t st = (hipStream_t)hip_stream;
-    const int D = draft->D, T = draft->T;
+    const int D = draft->D;
 
     // Rows never interact, and the two heads only share the noise (which each regenerates
-    // from the counters), so the call is cut into independent chains - (row chunk, head) -
-    // that run on their own streams.  One chain's memory-bound kernels and GEMM epilogues
-    // then fill the gaps of another chain's MFMA loops.  (Tying the chains into a fixed
-    // GEMM/row-kernel pipeline with events was measured and is slower: every cross-stream
-    // hand-over costs more than the overlap it buys.)  Chunks are multiples of 256 rows (the
-    // GEMM tile height), so every result is bit-identical to a single-chain run.  Fork and
-    // join are events on the caller's stream; the host is never synchronised.
+    // from the counters), so the call is cut into independent chains - (row chunk, head).
     SideStreams* side = side_streams(draft->device);
-    int n_chunks = row_chunks_setting();
-    if (n_chunks == 0) n_chunks = (R >= 8192) ? 2 : 1;
-    if (!side) n_chunks = 1;
-    int64_t chunk_rows = ((R + n_chunks - 1) / n_chunks + 255) / 256 * 256;
-    if (chunk_rows >= R) { n_chunks = 1; chunk_rows = R; }
-    n_chunks = (int)((R + chunk_rows - 1) / chunk_rows);
-
-    struct Chain { const csd_head* hd; HeadWs ws; int64_t r0, n; hipStream_t s; int which; };
+    int64_t chunk_rows;
+    const int n_chunks = plan_chunks(R, side != nullptr, &chunk_rows);
     Chain chains[8];
     int n_chains = 0;
     char* wp_ = (char*)workspace;
     for (int c = 0; c < n_chunks; ++c) {
         const int64_t r0 = c * chunk_rows, n = (R - r0 < chunk_rows) ? R - r0 : chunk_rows;
         for (int which = 0; which < 2; ++which) {
-            Chain& ch = chains[n_chains];
-            ch.hd = which ? target : draft; ch.r0 = r0; ch.n = n; ch.which = which;
+            Chain& ch = chains[n_chains++];
+            ch.hd = which ? target : draft; ch.n = n; ch.z = (which ? z_p : z_q) + r0 * ch.hd->C;
+            ch.row_offset = row_offset + (uint64_t)r0; ch.row_stride = 1; ch.row_shift = 0; ch.rng_stream = CSD_STREAM_TRAJ;
+            ch.summary = summary + r0 * (5 * D + 1); ch.is_target = which; ch.tokens = nullptr;
             wp_ = carve(ch.hd, n, wp_, &ch.ws);
-            ch.s = (n_chains == 0 || !side) ? st : side->stream[n_chains - 1];
-            ++n_chains;
         }
     }
-    if (side && n_chains > 1) {
-        HIP_TRY(hipEventRecord(side->fork, st));
-        for (int i = 1; i < n_chains; ++i) HIP_TRY(hipStreamWaitEvent(chains[i].s, side->fork, 0));
-    }
-    for (int i = 0; i < n_chains; i += 2) {     // x_T and the accumulators of both heads of a chunk
-        Chain& q = chains[i]; Chain& pch = chains[i + 1];
-        HIP_TRY(launch_init_x(q.ws.x, pch.ws.x, q.ws.acc, pch.ws.acc, q.n, D, T, seed, row_offset + q.r0, q.s));
-        if (q.s != pch.s) {                     // the target chain starts after its x_T is written
-            HIP_TRY(hipEventRecord(side->join[i], q.s));
-            HIP_TRY(hipStreamWaitEvent(pch.s, side->join[i], 0));
-        }
-    }
-    for (int i = 0; i < n_chains; ++i) {
-        Chain& ch = chains[i];
-        HIP_TRY(cond_embed(ch.hd, (ch.which ? z_p : z_q) + ch.r0 * ch.hd->C, ch.ws, ch.n, ch.s));
-    }
-    for (int t = T; t >= 1; --t) {
-        for (int i = 0; i < n_chains; ++i) {
-            Chain& ch = chains[i];
-            HIP_TRY(head_body(ch.hd, ch.ws, t, ch.n, ch.s));
-            TransArgs f = trans_args(ch.hd, ch.ws, t, ch.n);
-            f.seed = seed; f.row_offset = row_offset + ch.r0; f.tau = temperature;
-            f.summary = summary + ch.r0 * (5 * D + 1); f.is_target = ch.which;
-            HIP_TRY(launch_transition(f, ch.s));
-        }
-    }
-    if (side && n_chains > 1) {
-        for (int i = 1; i < n_chains; ++i) {
-            HIP_TRY(hipEventRecord(side->join[i], chains[i].s));
-            HIP_TRY(hipStreamWaitEvent(st, side->join[i], 0));
-        }
-    }
-    for (int i = 0; i < n_chains; i += 2) {
-        const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
-        HIP_TRY(launch_finish_summary(summary + chains[i].r0 * (5 * D + 1), chains[i].ws.acc, chains[i + 1].ws.acc,
-                                      ref_diff, chains[i].n, D, st));
-    }
+    int rc = run_chains(chains, n_chains, seed, temperature, st, side);
+    if (rc != CSD_OK) return rc;
+    const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
+    for (int i = 0; i < n_chains; i += 2)
+        HIP_TRY(launch_finish_summary(chains[i].summary, chains[i].ws.acc, chains[i + 1].ws.acc, ref_diff, chains[i].n, D,
+                                      0, 1, 0, st));
+    return CSD_OK;
+}
+
+int csd_denoise_draft(const csd_head_t* draft, const float* z_q, int64_t n_groups, int32_t gamma, int32_t position,
+                      uint64_t seed, uint64_t row_offset, float temperature, float* summary, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    if (!draft) return fail(CSD_EINVAL, "csd_denoise_draft: NULL head");
+    if (n_groups < 0 || gamma < 1 || position < 0 || position >= gamma)
+        return fail(CSD_EINVAL, "csd_denoise_draft: n_groups >= 0, gamma >= 1 and 0 <= position < gamma required");
+    if (!(temperature > 0.f)) return fail(CSD_EINVAL, "csd_denoise_draft: temperature must be > 0");
+    if (n_groups > (int64_t)(1 << 22) / gamma) return fail(CSD_EINVAL, "csd_denoise_draft: more than 2^22 rows in one call");
+    if (n_groups == 0) return CSD_OK;
+    if (!z_q || !summary) return fail(CSD_EINVAL, "csd_denoise_draft: NULL buffer");
+    int rc = check_ws("csd_denoise_draft", workspace, workspace_bytes, csd_workspace_bytes(draft, nullptr, n_groups));
+    if (rc != CSD_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Chain chains[8];
+    int n_chains = 0;
+    rc = run_single_head(draft, z_q, n_groups, seed, row_offset, gamma, position, CSD_STREAM_TRAJ, temperature, summary, 0,
+                         nullptr, workspace, st, chains, &n_chains);
+    if (rc != CSD_OK) return rc;
+    for (int i = 0; i < n_chains; ++i)      // park the draft's half of log Sigma in the last column
+        HIP_TRY(launch_finish_summary(chains[i].summary, chains[i].ws.acc, nullptr, 0.f, chains[i].n, draft->D, 1,
+                                      gamma, position, st));
+    return CSD_OK;
+}
+
+int csd_denoise_target(const csd_head_t* target, const csd_head_t* draft, const float* z_p, int64_t n_groups,
+                       int32_t gamma, uint64_t seed, uint64_t row_offset, float temperature, float* summary,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!target || !draft) return fail(CSD_EINVAL, "csd_denoise_target: NULL head");
+    if (n_groups < 0 || gamma < 1) return fail(CSD_EINVAL, "csd_denoise_target: n_groups >= 0 and gamma >= 1 required");
+    if (draft->D != target->D || draft->T != target->T || draft->device != target->device)
+        return fail(CSD_EINVAL, "csd_denoise_target: heads must share token_dim, n_steps and device");
+    if (!(temperature > 0.f)) return fail(CSD_EINVAL, "csd_denoise_target: temperature must be > 0");
+    if (n_groups > (int64_t)(1 << 22) / gamma) return fail(CSD_EINVAL, "csd_denoise_target: more than 2^22 rows in one call");
+    const int64_t R = n_groups * gamma;
+    if (R == 0) return CSD_OK;
+    if (!z_p || !summary) return fail(CSD_EINVAL, "csd_denoise_target: NULL buffer");
+    int rc = check_ws("csd_denoise_target", workspace, workspace_bytes, csd_workspace_bytes(nullptr, target, R));
+    if (rc != CSD_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    Chain chains[8];
+    int n_chains = 0;
+    rc = run_single_head(target, z_p, R, seed, row_offset, 1, 0, CSD_STREAM_TRAJ, temperature, summary, 1, nullptr,
+                         workspace, st, chains, &n_chains);
+    if (rc != CSD_OK) return rc;
+    const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
+    for (int i = 0; i < n_chains; ++i)
+        HIP_TRY(launch_finish_summary(chains[i].summary, nullptr, chains[i].ws.acc, ref_diff, chains[i].n, target->D, 2,
+                                      1, 0, st));
+    return CSD_OK;
+}
+
+int csd_sample(const csd_head_t* head, const float* z, int64_t n_rows, uint64_t seed, uint64_t row_offset,
+               int32_t rng_stream, float temperature, float* tokens, void* workspace, size_t workspace_bytes,
+               void* hip_stream) {
+    if (!head) return fail(CSD_EINVAL, "csd_sample: NULL head");
+    if (n_rows < 0 || n_rows > (1 << 22)) return fail(CSD_EINVAL, "csd_sample: n_rows out of range");
+    if (rng_stream != CSD_STREAM_TRAJ && rng_stream != CSD_STREAM_BONUS)
+        return fail(CSD_EINVAL, "csd_sample: rng_stream must be CSD_STREAM_TRAJ or CSD_STREAM_BONUS");
+    if (!(temperature > 0.f)) return fail(CSD_EINVAL, "csd_sample: temperature must be > 0");
+    if (n_rows == 0) return CSD_OK;
+    if (!z || !tokens) return fail(CSD_EINVAL, "csd_sample: NULL buffer");
+    int rc = check_ws("csd_sample", workspace, workspace_bytes, csd_workspace_bytes(head, nullptr, n_rows));
+    if (rc != CSD_OK) return rc;
+    Chain chains[8];
+    int n_chains = 0;
+    return run_single_head(head, z, n_rows, seed, row_offset, 1, 0, rng_stream, temperature, nullptr, 0, tokens, workspace,
+                           (hipStream_t)hip_stream, chains, &n_chains);
+}
+
+int csd_append_bonus(float* tokens, int32_t* n_out, const int32_t* n_accept, const float* bonus, int64_t n_groups,
+                     int32_t gamma, int32_t token_dim, void* hip_stream) {
+    if (n_groups < 0 || gamma < 1 || gamma > 64) return fail(CSD_EINVAL, "csd_append_bonus: n_groups >= 0 and 1 <= gamma <= 64 required");
+    if (token_dim != 4 && token_dim != 8 && token_dim != 16) return fail(CSD_EINVAL, "csd_append_bonus: token_dim must be 4, 8 or 16");
+    if (n_groups == 0) return CSD_OK;
+    if (!tokens || !n_out || !n_accept || !bonus) return fail(CSD_EINVAL, "csd_append_bonus: NULL buffer");
+    HIP_TRY(launch_append_bonus(tokens, n_out, n_accept, bonus, n_groups, gamma, token_dim, (hipStream_t)hip_stream));
     return CSD_OK;
 }
 

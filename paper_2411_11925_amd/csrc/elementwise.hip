@@ -298,7 +298,8 @@ __global__ void k_transition(TransArgs a) {
         return;
     }
     float nrm[4];
-    normals4(a.seed, a.row_offset + (uint64_t)r, (uint32_t)(a.t - 1), CSD_STREAM_TRAJ, (uint32_t)(d >> 2), nrm);
+    const int64_t sr = r * a.row_stride + a.row_shift;      // row of the call's summary / global row behind row_offset
+    normals4(a.seed, a.row_offset + (uint64_t)sr, (uint32_t)(a.t - 1), (uint32_t)a.rng_stream, (uint32_t)(d >> 2), nrm);
     const float eps = nrm[d & 3];
     const float lv = fmaf(o_v, a.coef.lhalf, a.coef.lmid);
     const float mu = fmaf(a.coef.cx, x, -a.coef.co * o_eps);
@@ -309,8 +310,10 @@ __global__ void k_transition(TransArgs a) {
 #pragma unroll
         for (int o = D / 2; o >= 1; o >>= 1) vs += __shfl_xor(vs, o, 64);
         if (d == 0) a.acc[r] += 0.5f * a.coef.lhalf * vs;
+    } else if (a.tokens) {
+        a.tokens[r * D + d] = xn;             // plain sampling: x_0 itself
     } else {
-        float* srow = a.summary + r * (5 * D + 1);
+        float* srow = a.summary + sr * (5 * D + 1);
         if (a.is_target) {
             srow[d] = mu; srow[D + d] = lv;
         } else {
@@ -332,39 +335,66 @@ hipError_t launch_transition(const TransArgs& a, hipStream_t st) {
     return hipGetLastError();
 }
 
-// ---------------------------------------------------------------- x_T = eps_T for both models
-__global__ void k_init_x(float* __restrict__ xq, float* __restrict__ xp, float* __restrict__ accq,
-                         float* __restrict__ accp, int64_t R, int D, int T, uint64_t seed, uint64_t row_offset) {
+// ---------------------------------------------------------------- x_T = eps_T, accumulator = 0
+__global__ void k_init_x(float* __restrict__ x, float* __restrict__ acc, int64_t R, int D, int T, uint64_t seed,
+                         uint64_t row_offset, int64_t row_stride, int64_t row_shift, int rng_stream) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one thread per (row, block of 4)
     const int nb = D >> 2;
     if (i >= R * nb) return;
     const int64_t r = i / nb; const int b = (int)(i % nb);
     float n[4];
-    normals4(seed, row_offset + (uint64_t)r, (uint32_t)T, CSD_STREAM_TRAJ, (uint32_t)b, n);
+    normals4(seed, row_offset + (uint64_t)(r * row_stride + row_shift), (uint32_t)T, (uint32_t)rng_stream, (uint32_t)b, n);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { xq[r * D + 4 * b + j] = n[j]; xp[r * D + 4 * b + j] = n[j]; }
-    if (b == 0) { accq[r] = 0.f; accp[r] = 0.f; }
+    for (int j = 0; j < 4; ++j) x[r * D + 4 * b + j] = n[j];
+    if (b == 0) acc[r] = 0.f;
 }
 
-hipError_t launch_init_x(float* xq, float* xp, float* accq, float* accp, int64_t R, int D, int T,
-                         uint64_t seed, uint64_t row_offset, hipStream_t st) {
+hipError_t launch_init_x(float* x, float* acc, int64_t R, int D, int T, uint64_t seed, uint64_t row_offset,
+                         int64_t row_stride, int64_t row_shift, int rng_stream, hipStream_t st) {
     const int64_t n = R * (D >> 2);
     if (n == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_init_x, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, xq, xp, accq, accp, R, D, T, seed, row_offset);
+    hipLaunchKernelGGL(k_init_x, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, acc, R, D, T, seed, row_offset,
+                       row_stride, row_shift, rng_stream);
     return hipGetLastError();
 }
 
-// log Sigma = (acc_q - acc_p) + (schedule reference difference, 0 for equal schedules)
+// The last column of the summary.  mode 0 (lockstep): log Sigma = (acc_q - acc_p) + ref, ref = the
+// schedule reference difference (0 for equal schedules).  mode 1 (draft phase): the draft's half,
+// acc_q, is parked there.  mode 2 (target phase): log Sigma = (parked - acc_p) + ref - the same
+// operations on the same values as mode 0, so both routes give the same bits.
 __global__ void k_finish_summary(float* __restrict__ summary, const float* __restrict__ accq,
-                                 const float* __restrict__ accp, float ref_diff, int64_t R, int D) {
+                                 const float* __restrict__ accp, float ref_diff, int64_t R, int D, int mode,
+                                 int64_t row_stride, int64_t row_shift) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r < R) summary[r * (5 * D + 1) + 5 * D] = (accq[r] - accp[r]) + ref_diff;
+    if (r >= R) return;
+    float* slot = summary + (r * row_stride + row_shift) * (5 * D + 1) + 5 * D;
+    if (mode == 0) *slot = (accq[r] - accp[r]) + ref_diff;
+    else if (mode == 1) *slot = accq[r];
+    else *slot = (*slot - accp[r]) + ref_diff;
 }
 
 hipError_t launch_finish_summary(float* summary, const float* accq, const float* accp, float ref_diff,
-                                 int64_t R, int D, hipStream_t st) {
+                                 int64_t R, int D, int mode, int64_t row_stride, int64_t row_shift, hipStream_t st) {
     if (R == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_finish_summary, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, summary, accq, accp, ref_diff, R, D);
+    hipLaunchKernelGGL(k_finish_summary, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, summary, accq, accp, ref_diff,
+                       R, D, mode, row_stride, row_shift);
+    return hipGetLastError();
+}
+
+// tokens [G, gamma+1, D]: groups with n_accept == gamma also emit the bonus token (Alg. 1, last line)
+__global__ void k_append_bonus(float* __restrict__ tokens, int32_t* __restrict__ n_out, const int32_t* __restrict__ n_accept,
+                               const float* __restrict__ bonus, int64_t G, int gamma, int D) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t g = i / D; const int d = (int)(i % D);
+    if (g >= G || n_accept[g] != gamma) return;
+    tokens[(g * (gamma + 1) + gamma) * D + d] = bonus[g * D + d];
+    if (d == 0) n_out[g] = gamma + 1;
+}
+
+hipError_t launch_append_bonus(float* tokens, int32_t* n_out, const int32_t* n_accept, const float* bonus,
+                               int64_t G, int gamma, int D, hipStream_t st) {
+    if (G == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_append_bonus, dim3((unsigned)((G * D + 255) / 256)), dim3(256), 0, st, tokens, n_out, n_accept, bonus, G, gamma, D);
     return hipGetLastError();
 }
 

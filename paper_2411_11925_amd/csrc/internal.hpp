@@ -113,16 +113,23 @@ struct TransArgs {
     float* acc;                // [R] running 1/2 sum_d (log sigma^2 - lmid_t), t >= 2
     StepCoef coef; int t;
     uint64_t seed, row_offset; float tau;
+    int64_t row_stride, row_shift;   // row r of this launch is row r*row_stride + row_shift of the call's summary,
+                                     // and global row row_offset + that of the noise counters
+    int rng_stream;                  // CSD_STREAM_TRAJ, or CSD_STREAM_BONUS for the target-only bonus sample
     float* summary; int is_target;   // t == 1: writes this head's part of the summary row
+    float* tokens;                   // optional [R,D]: t == 1 writes x_0 there instead (plain sampling)
     float* raw_out;            // optional [R,2D]: (eps_hat, v) for csd_head_eval; skips the transition
     float skip_coef;           // eps_skip_gain * sqrt(1 - abar_t), for raw_out only
 };
 hipError_t launch_transition(const TransArgs& a, hipStream_t st);
 
-hipError_t launch_init_x(float* xq, float* xp, float* accq, float* accp, int64_t R, int D, int T,
-                         uint64_t seed, uint64_t row_offset, hipStream_t st);
+hipError_t launch_init_x(float* x, float* acc, int64_t R, int D, int T, uint64_t seed, uint64_t row_offset,
+                         int64_t row_stride, int64_t row_shift, int rng_stream, hipStream_t st);
+// mode 0: lockstep (acc_q - acc_p + ref); 1: draft phase parks acc_q; 2: target phase finishes from the parked value
 hipError_t launch_finish_summary(float* summary, const float* accq, const float* accp, float ref_diff,
-                                 int64_t R, int D, hipStream_t st);
+                                 int64_t R, int D, int mode, int64_t row_stride, int64_t row_shift, hipStream_t st);
+hipError_t launch_append_bonus(float* tokens, int32_t* n_out, const int32_t* n_accept, const float* bonus,
+                               int64_t G, int gamma, int D, hipStream_t st);
 
 hipError_t launch_verify(const float* summary, int64_t G, int gamma, int D, uint64_t seed, uint64_t row_offset,
                          float tau, int32_t* n_accept, float* log_ratio, uint8_t* mask, hipStream_t st);

@@ -64,5 +64,12 @@ def test_argument_errors_without_device_work(B):
     assert lib.csd_rng_uniforms(1, 0, 0, 0, 0, None, None) == B.CSD_OK
     assert lib.csd_denoise_lockstep(None, None, None, None, 1, 1, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
     assert lib.csd_head_eval(None, None, None, 1, 1, None, None, 0, None) == B.CSD_EINVAL
+    assert lib.csd_denoise_draft(None, None, 1, 1, 0, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
+    assert lib.csd_denoise_target(None, None, None, 1, 1, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
+    assert lib.csd_sample(None, None, 1, 0, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
+    assert lib.csd_append_bonus(None, None, None, None, 4, 0, 16, None) == B.CSD_EINVAL
+    assert lib.csd_append_bonus(None, None, None, None, 4, 4, 5, None) == B.CSD_EINVAL
+    assert lib.csd_append_bonus(None, None, None, None, 4, 4, 16, None) == B.CSD_EINVAL      # NULL buffers
+    assert lib.csd_append_bonus(None, None, None, None, 0, 4, 16, None) == B.CSD_OK          # empty: no-op
     assert lib.csd_workspace_bytes(None, None, 10) == 0
     lib.csd_free_head(None)
