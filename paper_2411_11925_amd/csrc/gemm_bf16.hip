@@ -354,7 +354,10 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
         // the whole path, where several chains share the chip; it is used only where 256 does not divide N)
         if (g.M >= 2048 && g.N % 256 == 0) variant = 9;
         else if (g.M >= 2048 && g.N % 192 == 0) variant = 8;
-        else variant = (g.N % 128 == 0 && g.M >= 256) ? 2 : 3;
+        // below that the launch is latency-bound and wants many small workgroups: the 64x64 tile beats
+        // 128x128 at every M measured (one head pass at 256 / 1024 rows: 263 / 290 us against 343 / 366),
+        // and a deeper ring of slabs buys nothing there
+        else variant = 3;
     }
     if ((variant == 0 || variant == 1 || variant == 9) && g.N % 256 != 0) variant = (g.N % 192 == 0 && g.M >= 2048) ? 8 : 3;
     if (variant == 8 && g.N % 192 != 0) variant = 3;
