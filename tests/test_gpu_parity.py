@@ -354,3 +354,47 @@ def test_reject_heavy_ragged_rows_bf16(B):
     """gamma = 8, a row count that is no multiple of any tile (ragged tail)."""
     wl = S.WORKLOADS["reject"]
     _sampled_rows_check(B, wl, 8 * 300, [0, 2304], H.BF16_TOL, check_decisions=False)
+
+
+# ------------------------------------------------- schedules given as tables ----
+def test_table_schedule_and_unequal_schedules_f32(B):
+    """CSD_TABLE with the cosine schedule's own alpha_bar reproduces CSD_COSINE; a draft on a
+    different (linear-beta) schedule than the target exercises the schedule part of log Sigma
+    (the difference of the two heads' log sigma^2 at v = 0), against the oracle."""
+    wl = S.WORKLOADS["tiny"].with_(gamma=2)
+    tb, db, ds = wl.heads(0.05)
+    T, G, gamma, D = wl.n_steps, 40, 2, 16
+    zq, zp = wl.conds(128)
+    zq, zp = zq[:G * gamma], zp[:G * gamma]
+    cos = O.cosine_schedule(T)
+    mk = lambda ab: B.make_cfg(16, 64, 128, 2, T, B.CSD_F32, alpha_bar=ab, eps_skip_gain=wl.eps_skip_gain)
+    hq_c, hp_c = B.csd_init_head(mk(None), db), B.csd_init_head(mk(None), tb)
+    hq_t, hp_t = B.csd_init_head(mk(cos.abar), db), B.csd_init_head(mk(cos.abar), tb)
+    a = B.csd_denoise_lockstep(hq_c, hp_c, _t(zq), _t(zp), G, gamma, 5).cpu().numpy()
+    b = B.csd_denoise_lockstep(hq_t, hp_t, _t(zq), _t(zp), G, gamma, 5).cpu().numpy()
+    assert H.rel_err(b[:, 4 * D:5 * D], a[:, 4 * D:5 * D]) < 1e-5 and np.max(np.abs(a[:, -1] - b[:, -1])) < 1e-4
+    # draft on a linear-beta schedule
+    beta = np.linspace(1e-3, 0.35, T)
+    abar_lin = np.concatenate([[1.0], np.cumprod(1.0 - beta)])
+    lin = O.schedule_from_abar(abar_lin)
+    ocfg = O.HeadCfg(16, 64, 128, 2, T, eps_skip_gain=wl.eps_skip_gain)
+    oq, op = O.Head(ocfg, db, lin), O.Head(ocfg, tb, cos)
+    want, _ = O.denoise_lockstep(oq, op, zq, zp, seed=5)
+    hq_l = B.csd_init_head(mk(abar_lin), db)
+    got = B.csd_denoise_lockstep(hq_l, hp_c, _t(zq), _t(zp), G, gamma, 5).cpu().numpy()
+    mu_p, lv_p, mu_q, lv_q, x0, ls = O.split_summary(want, D)
+    g = O.split_summary(got, D)
+    assert H.rel_err(g[4], x0) < H.F32_TOL and H.rel_err(g[2], mu_q) < H.F32_TOL
+    assert np.max(np.abs(g[3] - lv_q)) < 1e-3 and np.max(np.abs(g[1] - lv_p)) < 1e-3
+    assert np.abs(ls).max() > 1.0                      # the schedule part is really there
+    assert np.max(np.abs(g[5] - ls)) < H.F32_TOL * 10 * max(1.0, np.abs(ls).max())
+    # and the split-phase route carries the same reference difference
+    summ = torch.zeros((G * gamma, 5 * D + 1), device=DEV)
+    for i in range(gamma):
+        B.csd_denoise_draft(hq_l, _t(zq.reshape(G, gamma, -1)[:, i]), G, gamma, i, 5, 0, 1.0, summ)
+    B.csd_denoise_target(hp_c, hq_l, _t(zp), G, gamma, 5, 0, 1.0, summ)
+    assert np.array_equal(summ.cpu().numpy(), got)
+    with pytest.raises(B.CsdError):                    # alpha_bar must decrease strictly from 1
+        B.csd_init_head(mk(np.concatenate([[1.0], np.full(T, 0.5)])), db)
+    for h in (hq_c, hp_c, hq_t, hp_t, hq_l):
+        h.free()
