@@ -249,6 +249,8 @@ class HeadCfg:
     ln_eps: float = 1e-6
     t_scale: float | None = None    # default 1000 / T
     eps_skip_gain: float = 0.0      # eps_hat = gain * sqrt(1-abar_t) * x_t + o[:D]
+    sampler: str = "ddpm"           # "ddpm" (Eq. 3, learned-range variance) | "ddim" (App., other samplers)
+    ddim_eta: float = 1.0           # DDIM: sigma_t^2 = eta^2 * beta~_t
 
 
 def head_param_shapes(cfg: HeadCfg):
@@ -341,6 +343,14 @@ class Head:
 # --------------------------------------------------------------------------
 # Gaussian transition (Eq. 3) and its log-density
 # --------------------------------------------------------------------------
+def head_transition(head: "Head", x, t: int, eps_hat, v):
+    """(mu_t, log sigma_t^2) of the head's sampler: Eq. 3 (DDPM) or the DDIM step."""
+    if head.cfg.sampler == "ddim":
+        return ddim_transition_params(head.sched, x, t, eps_hat, head.cfg.ddim_eta)
+    assert head.cfg.sampler == "ddpm"
+    return transition_params(head.sched, x, t, eps_hat, v)
+
+
 def transition_params(sched: Schedule, x, t: int, eps_hat, v):
     """mu_theta(x_t,t) and log of the diagonal of Sigma_theta(x_t,t):
     mu = (x_t - beta_t/sqrt(1-abar_t) eps_hat)/sqrt(alpha_t);
@@ -349,6 +359,20 @@ def transition_params(sched: Schedule, x, t: int, eps_hat, v):
     f = (v + 1.0) / 2.0
     logvar = f * sched.log_beta[t] + (1.0 - f) * sched.log_beta_tilde_clip[t]
     return mu, logvar
+
+
+def ddim_transition_params(sched: Schedule, x, t: int, eps_hat, eta: float):
+    """The DDIM reverse step as a Gaussian p(x_{t-1}|x_t) (appendix on other samplers; the
+    published DDIM update): with x0_hat = (x_t - sqrt(1-abar_t) eps_hat)/sqrt(abar_t),
+      mu = sqrt(abar_{t-1}) x0_hat + sqrt(1 - abar_{t-1} - sigma_t^2) eps_hat,
+      sigma_t^2 = eta^2 (1-abar_{t-1})/(1-abar_t) (1 - abar_t/abar_{t-1}) = eta^2 beta~_t,
+    the variance is fixed (the head's v is not used).  At t = 1 beta~_1 = 0 is replaced by
+    beta~_2 as in the DDPM path (the final step has to be a density), and the coefficient of
+    eps_hat under the root is clamped at 0."""
+    var = eta * eta * math.exp(sched.log_beta_tilde_clip[t])
+    x0_hat = (x - math.sqrt(1.0 - sched.abar[t]) * eps_hat) / math.sqrt(sched.abar[t])
+    mu = math.sqrt(sched.abar[t - 1]) * x0_hat + math.sqrt(max(0.0, 1.0 - sched.abar[t - 1] - var)) * eps_hat
+    return mu, np.full_like(np.asarray(x, dtype=np.float64), math.log(var))
 
 
 def gaussian_logpdf(x, mu, logvar, tau: float = 1.0):
@@ -399,8 +423,8 @@ def denoise_lockstep(draft: Head, target: Head, z_q, z_p, seed: int,
     for t in range(T, 0, -1):
         eh_q, v_q = draft.forward(x_q, t, e_q)
         eh_p, v_p = target.forward(x_p, t, e_p)
-        mu_q, lv_q = transition_params(draft.sched, x_q, t, eh_q, v_q)
-        mu_p, lv_p = transition_params(target.sched, x_p, t, eh_p, v_p)
+        mu_q, lv_q = head_transition(draft, x_q, t, eh_q, v_q)
+        mu_p, lv_p = head_transition(target, x_p, t, eh_p, v_p)
         eps_t = eps(t - 1)
         eps_t_p = eps_t if aligned else normals(seed ^ 0x5DEECE66D, rows, t - 1, STREAM_TRAJ, D)
         xn_q = mu_q + tau * np.exp(0.5 * lv_q) * eps_t
@@ -443,7 +467,7 @@ def head_trajectory(head: Head, z, global_rows, seed: int, tau: float = 1.0,
     half = np.zeros(z.shape[0])
     for t in range(T, 0, -1):
         eh, v = head.forward(x, t, e)
-        mu, lv = transition_params(head.sched, x, t, eh, v)
+        mu, lv = head_transition(head, x, t, eh, v)
         xn = mu + tau * np.exp(0.5 * lv) * normals(seed, rows, t - 1, stream, D)
         if t >= 2:
             half += 0.5 * np.sum(lv, axis=-1)

@@ -563,3 +563,58 @@ def test_append_bonus_only_for_fully_accepted_groups():
             assert np.array_equal(tokens[g, gamma], bonus[g]) and np.array_equal(tokens[g, :gamma], before[g, :gamma])
         else:
             assert np.array_equal(tokens[g], before[g])
+
+
+# ------------------------------------------------------ DDIM as the sampler ----
+def test_ddim_step_preserves_the_marginals_and_reduces_to_ddpm():
+    """What defines the DDIM update: if eps_hat is the true noise of
+    x_t = sqrt(abar_t) x_0 + sqrt(1-abar_t) eps, its mean is
+    sqrt(abar_{t-1}) x_0 + sqrt(1-abar_{t-1}-sigma_t^2) eps with sigma_t^2 = eta^2 beta~_t, so
+    mean-noise power plus sigma_t^2 is the marginal's 1-abar_{t-1} for every eta; and eta = 1
+    is the DDPM posterior: the Eq. 3 mean with the variance at its lower end (v = -1)."""
+    s = O.cosine_schedule(50)
+    rng = np.random.default_rng(0)
+    x0, eps = rng.normal(size=(6, 4)), rng.normal(size=(6, 4))
+    for t in (50, 17, 2):
+        xt = math.sqrt(s.abar[t]) * x0 + math.sqrt(1 - s.abar[t]) * eps
+        for eta in (0.0, 0.3, 1.0):
+            if eta == 0.0:
+                # (the oracle takes log sigma^2, so eta = 0 is checked through the mean only)
+                mu, _ = O.ddim_transition_params(s, xt, t, eps, 1e-12)
+            else:
+                mu, lv = O.ddim_transition_params(s, xt, t, eps, eta)
+                assert np.allclose(lv, math.log(eta * eta * s.beta_tilde[t]), rtol=1e-12)
+            var = (eta * eta if eta else 0.0) * s.beta_tilde[t]
+            want = math.sqrt(s.abar[t - 1]) * x0 + math.sqrt(1 - s.abar[t - 1] - var) * eps
+            assert np.allclose(mu, want, rtol=1e-9, atol=1e-12)
+        # eta = 1 against the (already pinned) DDPM transition for an arbitrary eps_hat
+        eh = rng.normal(size=(6, 4))
+        mu_i, lv_i = O.ddim_transition_params(s, xt, t, eh, 1.0)
+        mu_p, lv_p = O.transition_params(s, xt, t, eh, -np.ones((6, 4)))
+        assert np.allclose(mu_i, mu_p, rtol=1e-9, atol=1e-12) and np.allclose(lv_i, lv_p, rtol=1e-12)
+    # the final step keeps a density: sigma_1^2 = eta^2 beta~_2, direction term clamped to 0
+    mu, lv = O.ddim_transition_params(s, x0, 1, eps, 0.5)
+    assert np.allclose(lv, math.log(0.25 * s.beta_tilde[2]))
+    assert np.allclose(mu, (x0 - math.sqrt(1 - s.abar[1]) * eps) / math.sqrt(s.abar[1]))
+
+
+def test_ddim_heads_run_the_whole_path_with_sigma_factor_one():
+    """Two heads on the same schedule with the DDIM sampler have equal, fixed variances:
+    log Sigma is exactly 0 and the ratio is the final-step density ratio alone; identical
+    heads still accept everything."""
+    shape = S.HeadShape(8, 6, 16, 2)
+    tb = S.head_weights(shape, 7, 0.3, 0.1)
+    db = S.perturbed_copy(tb, shape, 8, 0.2, 0.3)
+    cfg = O.HeadCfg(8, 6, 16, 2, 6, eps_skip_gain=1.0, sampler="ddim", ddim_eta=0.7)
+    tgt, drf = O.Head(cfg, tb), O.Head(cfg, db)
+    zq, zp = S.cond_vectors(24, 6, 3, add_std=0.3)
+    summ, ex = O.denoise_lockstep(drf, tgt, zq, zp, seed=9)
+    assert np.all(summ[:, -1] == 0.0)
+    assert np.allclose(ex["log_sigma_full"], 0.0, atol=1e-9)        # the exponentials cancel too (Eq. 6)
+    ell = O.log_ratio(summ, 8)
+    mu_p, lv_p, mu_q, lv_q, x0, _ = O.split_summary(summ, 8)
+    assert np.allclose(ell, stats.norm.logpdf(x0, mu_p, np.exp(0.5 * lv_p)).sum(1)
+                       - stats.norm.logpdf(x0, mu_q, np.exp(0.5 * lv_q)).sum(1))
+    same, _ = O.denoise_lockstep(tgt, tgt, zq, zq, seed=9)
+    n_acc, ell2, mask, _ = O.verify(same, 6, 4, 9)
+    assert np.all(ell2 == 0.0) and np.all(n_acc == 4)
