@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--dtype", default=None, choices=[None, "bf16", "f32"])
     ap.add_argument("--rows", type=int, default=0, help="rows per step (default: the whole workload)")
     ap.add_argument("--oracle-rows", type=int, default=128, help="rows of the CPU-oracle sample (0: skip)")
+    ap.add_argument("--ddim-eta", type=float, default=None, help="use the DDIM sampler with this eta (default: DDPM)")
     ap.add_argument("--no-latency-shape", action="store_true", help="skip the split-phase latency-shape figure")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 256 MiB device to device once (a kernel of known "
@@ -78,7 +79,7 @@ def main():
     tb, db, ds = wl.heads()
     gd = B.CSD_BF16 if dtype == "bf16" else B.CSD_F32
     mk = lambda sh: B.make_cfg(sh.token_dim, sh.cond_dim, sh.width, sh.n_blocks, wl.n_steps, gd,
-                               eps_skip_gain=wl.eps_skip_gain)
+                               eps_skip_gain=wl.eps_skip_gain, ddim_eta=a.ddim_eta)
     h_q, h_p = B.csd_init_head(mk(ds), db), B.csd_init_head(mk(wl.target), tb)
     zq_h, zp_h = wl.conds(((R + 63) // 64) * 64)
     z_q, z_p = torch.from_numpy(zq_h[:R]).to(dev), torch.from_numpy(zp_h[:R]).to(dev)
@@ -153,7 +154,8 @@ def main():
         "config": {"workload": "%s: target %dx%d, draft %dx%d, C=%d, T=%d, rows/step=%d (G=%d, gamma=%d)" % (
             wl.name, wl.target.n_blocks, wl.target.width, ds.n_blocks, ds.width, wl.target.cond_dim,
             wl.n_steps, R, G, gamma), "rows_per_step": R, "gamma": gamma, "out_scale": wl.out_scale,
-            "eps_skip_gain": wl.eps_skip_gain},
+            "eps_skip_gain": wl.eps_skip_gain,
+            "sampler": "ddpm" if a.ddim_eta is None else "ddim(eta=%g)" % a.ddim_eta},
         "wall_s": wall,
         "whole_path": {"algorithmic_TFLOP_per_s": flops_row * R * a.steps / (ms / 1e3) / 1e12,
                        "frac_of_peak": flops_row * R * a.steps / (ms / 1e3) / 1e12 / peak,
@@ -212,8 +214,9 @@ def main():
         except Exception:
             cores = os.cpu_count()
         n = min(a.oracle_rows // gamma * gamma, R)
+        samp = dict(sampler="ddim", ddim_eta=a.ddim_eta) if a.ddim_eta is not None else {}
         ocfg = lambda sh: O.HeadCfg(sh.token_dim, sh.cond_dim, sh.width, sh.n_blocks, wl.n_steps,
-                                    eps_skip_gain=wl.eps_skip_gain)
+                                    eps_skip_gain=wl.eps_skip_gain, **samp)
         t0 = time.perf_counter()
         o_q, o_p = O.Head(ocfg(ds), db), O.Head(ocfg(wl.target), tb)
         t_init = time.perf_counter() - t0

@@ -48,6 +48,16 @@ extern "C" {
 #define CSD_COSINE 0           /* native T-step cosine schedule, betas clipped at 0.999 */
 #define CSD_TABLE  1           /* caller supplies alpha_bar[0..T] */
 
+/* The head's sampler: the Gaussian p(x_{t-1}|x_t) of one reverse step (appendix "More
+ * variants of diffusion model": any sampler with an explicit step density fits).
+ * DDPM: Eq. 3 with the learned-range variance (definition below).
+ * DDIM: mu = sqrt(abar_{t-1}) x0_hat + sqrt(max(0, 1-abar_{t-1}-sigma_t^2)) eps_hat with
+ *       x0_hat = (x_t - sqrt(1-abar_t) eps_hat)/sqrt(abar_t) and the fixed variance
+ *       sigma_t^2 = eta^2 beta~_t (beta~_1 := beta~_2, so the final step keeps a density);
+ *       the head's v output is not used; eta = 1 is the DDPM posterior. */
+#define CSD_SAMPLER_DDPM 0
+#define CSD_SAMPLER_DDIM 1
+
 #define CSD_TIME_FEATURES 256  /* sinusoidal features of the step index */
 
 /* streams of the counter-based generator (third counter word = slot | stream << 16) */
@@ -93,12 +103,12 @@ typedef struct {
     int32_t n_steps;         /* T */
     int32_t gemm_dtype;      /* CSD_F32 | CSD_BF16 */
     int32_t schedule;        /* CSD_COSINE | CSD_TABLE */
-    int32_t reserved;        /* must be 0 */
+    int32_t sampler;         /* CSD_SAMPLER_DDPM (0) | CSD_SAMPLER_DDIM */
     const double* alpha_bar; /* host [n_steps+1], alpha_bar[0]=1, strictly decreasing; CSD_TABLE only */
     float ln_eps;            /* <= 0 selects 1e-6 */
     float t_scale;           /* <= 0 selects 1000/T */
     float eps_skip_gain;     /* 0 = plain eps-prediction */
-    float reserved2;         /* must be 0 */
+    float ddim_eta;          /* CSD_SAMPLER_DDIM: sigma_t^2 = eta^2 beta~_t, eta > 0; else must be 0 */
 } csd_head_cfg_t;
 
 /* Number of fp32 values in the packed weight blob of `cfg`, 0 if cfg is invalid. */

@@ -27,6 +27,7 @@ CSD_F32, CSD_BF16 = 0, 1
 CSD_COSINE, CSD_TABLE = 0, 1
 CSD_STREAM_TRAJ, CSD_STREAM_ACCEPT_U, CSD_STREAM_RESAMPLE_N, CSD_STREAM_RESAMPLE_U = 0, 1, 2, 3
 CSD_STREAM_BONUS = 4
+CSD_SAMPLER_DDPM, CSD_SAMPLER_DDIM = 0, 1
 CSD_FLAG_CAP, CSD_FLAG_NONFINITE = 1, 2
 
 EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_workspace_bytes",
@@ -38,9 +39,9 @@ EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_workspace_b
 class csd_head_cfg_t(Structure):
     _fields_ = [("token_dim", c_int32), ("cond_dim", c_int32), ("width", c_int32),
                 ("n_blocks", c_int32), ("n_steps", c_int32), ("gemm_dtype", c_int32),
-                ("schedule", c_int32), ("reserved", c_int32), ("alpha_bar", POINTER(c_double)),
+                ("schedule", c_int32), ("sampler", c_int32), ("alpha_bar", POINTER(c_double)),
                 ("ln_eps", c_float), ("t_scale", c_float), ("eps_skip_gain", c_float),
-                ("reserved2", c_float)]
+                ("ddim_eta", c_float)]
 
 
 _lib.csd_last_error.restype = c_char_p
@@ -119,10 +120,12 @@ def _ptr(t) -> int:
 
 
 def make_cfg(token_dim, cond_dim, width, n_blocks, n_steps, gemm_dtype=CSD_F32, alpha_bar=None,
-             ln_eps=0.0, t_scale=0.0, eps_skip_gain=0.0):
+             ln_eps=0.0, t_scale=0.0, eps_skip_gain=0.0, ddim_eta=None):
+    """ddim_eta=None: the DDPM sampler; a positive value: DDIM with sigma_t^2 = eta^2 beta~_t."""
     cfg = csd_head_cfg_t(token_dim, cond_dim, width, n_blocks, n_steps, gemm_dtype,
-                         CSD_COSINE if alpha_bar is None else CSD_TABLE, 0, None,
-                         ln_eps, t_scale, eps_skip_gain, 0.0)
+                         CSD_COSINE if alpha_bar is None else CSD_TABLE,
+                         CSD_SAMPLER_DDPM if ddim_eta is None else CSD_SAMPLER_DDIM, None,
+                         ln_eps, t_scale, eps_skip_gain, 0.0 if ddim_eta is None else ddim_eta)
     if alpha_bar is not None:
         arr = np.ascontiguousarray(alpha_bar, dtype=np.float64)
         cfg._keep = arr

@@ -38,7 +38,9 @@ bool cfg_ok(const csd_head_cfg_t* c, const char** why) {
     if (c->gemm_dtype != CSD_F32 && c->gemm_dtype != CSD_BF16) { *why = "gemm_dtype must be CSD_F32 or CSD_BF16"; return false; }
     if (c->schedule != CSD_COSINE && c->schedule != CSD_TABLE) { *why = "schedule must be CSD_COSINE or CSD_TABLE"; return false; }
     if (c->schedule == CSD_TABLE && !c->alpha_bar) { *why = "CSD_TABLE needs alpha_bar"; return false; }
-    if (c->reserved != 0 || c->reserved2 != 0.f) { *why = "reserved fields must be 0"; return false; }
+    if (c->sampler != CSD_SAMPLER_DDPM && c->sampler != CSD_SAMPLER_DDIM) { *why = "sampler must be CSD_SAMPLER_DDPM or CSD_SAMPLER_DDIM"; return false; }
+    if (c->sampler == CSD_SAMPLER_DDPM && c->ddim_eta != 0.f) { *why = "ddim_eta must be 0 with CSD_SAMPLER_DDPM"; return false; }
+    if (c->sampler == CSD_SAMPLER_DDIM && !(c->ddim_eta > 0.f && c->ddim_eta <= 16.f)) { *why = "ddim_eta must be in (0,16]"; return false; }
     if (!(c->eps_skip_gain == c->eps_skip_gain)) { *why = "eps_skip_gain is NaN"; return false; }
     return true;
 }
@@ -400,11 +402,21 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
     lbt[1] = (T >= 2) ? lbt[2] : lb[1];       // posterior variance is 0 at t = 1: clipped to the next one
     h->ref_log_sigma = 0.0;
     for (int t = 1; t <= T; ++t) {
+        // every sampler here is mu = a x_t + b eps_hat, log sigma^2 = lmid + v lhalf; with the skip
+        // eps_hat = gain sqrt(1-abar_t) x_t + o the kernels use mu = cx x_t - co o
         const double alpha = abar[t] / abar[t - 1], beta = 1.0 - alpha;
-        const double co = beta / (std::sqrt(1.0 - abar[t]) * std::sqrt(alpha));
-        const double cx = 1.0 / std::sqrt(alpha) - co * (double)cfg->eps_skip_gain * std::sqrt(1.0 - abar[t]);
-        h->coef[t] = StepCoef{(float)cx, (float)co, (float)(0.5 * (lb[t] + lbt[t])), (float)(0.5 * (lb[t] - lbt[t]))};
-        if (t >= 2) h->ref_log_sigma += 0.5 * D * 0.5 * (lb[t] + lbt[t]);
+        double a = 1.0 / std::sqrt(alpha), b, lmid, lhalf;
+        if (cfg->sampler == CSD_SAMPLER_DDIM) {
+            const double var = (double)cfg->ddim_eta * (double)cfg->ddim_eta * std::exp(lbt[t]);
+            b = std::sqrt(std::fmax(0.0, 1.0 - abar[t - 1] - var)) - std::sqrt(1.0 - abar[t]) / std::sqrt(alpha);
+            lmid = std::log(var); lhalf = 0.0;
+        } else {
+            b = -beta / (std::sqrt(1.0 - abar[t]) * std::sqrt(alpha));
+            lmid = 0.5 * (lb[t] + lbt[t]); lhalf = 0.5 * (lb[t] - lbt[t]);
+        }
+        const double cx = a + b * (double)cfg->eps_skip_gain * std::sqrt(1.0 - abar[t]);
+        h->coef[t] = StepCoef{(float)cx, (float)(-b), (float)lmid, (float)lhalf};
+        if (t >= 2) h->ref_log_sigma += 0.5 * D * lmid;
     }
     h->skip_sqrt.assign(T + 1, 0.f);
     for (int t = 1; t <= T; ++t) h->skip_sqrt[t] = (float)((double)cfg->eps_skip_gain * std::sqrt(1.0 - abar[t]));

@@ -13,18 +13,19 @@ BF16_TOL = 2e-2    # bf16-MFMA path vs fp64 oracle fed the bf16-rounded weights
 BAND = 1e-3        # decisions are exempt where |log u - log ratio| < BAND
 
 
-def oracle_heads(wl: S.Workload, bias_std: float = 0.0):
+def oracle_heads(wl: S.Workload, bias_std: float = 0.0, ddim_eta: float | None = None):
     tb, db, ds = wl.heads(bias_std)
+    samp = dict(sampler="ddim", ddim_eta=ddim_eta) if ddim_eta is not None else {}
     mk = lambda sh: O.HeadCfg(sh.token_dim, sh.cond_dim, sh.width, sh.n_blocks, wl.n_steps,
-                              eps_skip_gain=wl.eps_skip_gain)
+                              eps_skip_gain=wl.eps_skip_gain, **samp)
     return O.Head(mk(ds), db), O.Head(mk(wl.target), tb), (db, ds, tb)
 
 
-def device_heads(B, wl: S.Workload, blobs, dtype: str | None = None):
+def device_heads(B, wl: S.Workload, blobs, dtype: str | None = None, ddim_eta: float | None = None):
     db, ds, tb = blobs
     gd = B.CSD_BF16 if (dtype or wl.gemm_dtype) == "bf16" else B.CSD_F32
     mk = lambda sh: B.make_cfg(sh.token_dim, sh.cond_dim, sh.width, sh.n_blocks, wl.n_steps, gd,
-                               eps_skip_gain=wl.eps_skip_gain)
+                               eps_skip_gain=wl.eps_skip_gain, ddim_eta=ddim_eta)
     return B.csd_init_head(mk(ds), db), B.csd_init_head(mk(wl.target), tb)
 
 
