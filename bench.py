@@ -95,7 +95,7 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
-    launches_per_step = 2 * wl.n_steps * (ds.n_blocks + wl.target.n_blocks) // 2
+    launches_per_step = 2 * wl.n_steps          # one stacked modulation GEMM per head, step and row chunk
     B.csd_profile_enable(min(4 * a.steps * launches_per_step + 16, 1 << 18))   # up to 4 row chunks per call
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
@@ -115,10 +115,11 @@ def main():
         m_iso = R // 2 if R >= 8192 else R
         tot_ms, tot_fl = 0.0, 0.0
         for sh in (wl.target, ds):
+            n_mod = 3 * sh.n_blocks * sh.width
             A_ = torch.randn(m_iso, sh.width, device=dev).bfloat16()
-            W_ = (torch.randn(3 * sh.width, sh.width, device=dev) / sh.width ** 0.5).bfloat16()
-            b_ = torch.zeros(3 * sh.width, device=dev)
-            C_ = torch.empty(m_iso, 3 * sh.width, device=dev, dtype=torch.bfloat16)
+            W_ = (torch.randn(n_mod, sh.width, device=dev) / sh.width ** 0.5).bfloat16()
+            b_ = torch.zeros(n_mod, device=dev)
+            C_ = torch.empty(m_iso, n_mod, device=dev, dtype=torch.bfloat16)
             for _ in range(3):
                 B.csd_gemm_bf16(A_, W_, b_, 0, C=C_)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -127,7 +128,8 @@ def main():
                 B.csd_gemm_bf16(A_, W_, b_, 0, C=C_)
             e1.record(); torch.cuda.synchronize()
             tot_ms += e0.elapsed_time(e1) / 20
-            tot_fl += 2.0 * m_iso * 3 * sh.width * sh.width
+            tot_fl += 2.0 * m_iso * n_mod * sh.width
+            del A_, W_, b_, C_
         iso = tot_fl / (tot_ms / 1e3) / 1e12
     if a.calibration_copy:
         src = torch.ones(64 << 20, dtype=torch.float32, device=dev)
@@ -141,11 +143,14 @@ def main():
     tokens_per_s = R * a.steps / (ms / 1e3)
     achieved = (k_flops / k_n) / (k_ms / k_n / 1e3) / 1e12 if k_n else 0.0
     peak = PEAK[dtype]
-    # modulation GEMM per launch: reads s [M,W] and the weights [3W,W], writes [M,3W]; bf16 = 2 bytes
+    # modulation GEMM per launch (all L blocks of a head at once): reads s [M,W] and the stacked
+    # weights [3LW,W], writes [M,3LW]; bf16 = 2 bytes.  Averages over the two heads' launches.
     esz = 2 if dtype == "bf16" else 4
-    m_launch = k_flops / k_n / (3 * (wl.target.width ** 2 + ds.width ** 2)) if k_n else 0   # mean rows per launch
-    alg_bytes = esz * (m_launch * (wl.target.width + ds.width) / 2 * 4
-                       + 3 * (wl.target.width ** 2 + ds.width ** 2) / 2) if k_n else None
+    lw2 = wl.target.n_blocks * wl.target.width ** 2 + ds.n_blocks * ds.width ** 2
+    lw1 = wl.target.n_blocks * wl.target.width + ds.n_blocks * ds.width
+    m_launch = k_flops / k_n / (3 * lw2) if k_n else 0          # mean rows per launch
+    alg_bytes = esz * (m_launch * (wl.target.width + ds.width) / 2 + 3 * lw2 / 2
+                       + m_launch * 3 * lw1 / 2) if k_n else None
     mask_h, trips_h, nacc_h = mask.cpu().numpy(), trips.cpu().numpy(), n_acc.cpu().numpy()
     res = {
         "metric": "verified tokens/sec (denoise+verify+resample)", "value": tokens_per_s, "unit": "tokens/s",
@@ -163,7 +168,7 @@ def main():
         "acceptance": {"row_accept_rate": float(mask_h.mean()), "mean_accepted_prefix": float(nacc_h.mean()),
                        "resample_trips_mean": float(trips_h[trips_h > 0].mean()) if (trips_h > 0).any() else 0.0,
                        "resample_trips_max": int(trips_h.max()), "cap_flags": int((flags.cpu().numpy() & 1).sum())},
-        "roofline": {"bound": "mfma" if dtype == "bf16" else "alu", "kernel": "modulation GEMM [R,W]x[W,3W]",
+        "roofline": {"bound": "mfma" if dtype == "bf16" else "alu", "kernel": "modulation GEMM of all L blocks [M,W]x[W,3LW]",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "launches_timed": k_n, "avg_launch_ms": k_ms / k_n if k_n else None,
                      "algorithmic_bytes_per_launch": alg_bytes,

@@ -57,7 +57,7 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // device buffers of one head for R rows, carved from the caller's workspace
 struct HeadWs {
-    float* e; void* s; void* mod[2]; float* fm; float* h; void* u; void* a; void* y; float* o; float* x; float* acc;
+    float* e; void* s; void* mod; float* fm; float* h; void* u; void* a; void* y; float* o; float* x; float* acc;
 };
 
 size_t head_ws_bytes(const csd_head* hd, int64_t R) {
@@ -65,7 +65,7 @@ size_t head_ws_bytes(const csd_head* hd, int64_t R) {
     size_t n = 0;
     n += align_up(r * W * 4, 256);          // e
     n += align_up(r * W * act, 256);        // s
-    n += 2 * align_up(r * 3 * W * act, 256);  // mod of the current and the previous block
+    n += align_up(r * 3 * W * hd->L * act, 256);  // mod: (shift, scale, gate) of all L blocks, [R, L*3W]
     n += align_up(r * 2 * W * 4, 256);      // fm (fp32 in both modes)
     n += align_up(r * W * 4, 256);          // h
     n += align_up(r * W * 4, 256);          // u (fp32, bf16, or the [hi|lo] bf16 pair of the last layer)
@@ -81,8 +81,7 @@ char* carve(const csd_head* hd, int64_t R, char* p, HeadWs* ws) {
     auto take = [&](size_t bytes) { char* q = p; p += align_up(bytes, 256); return q; };
     ws->e = (float*)take(r * W * 4);
     ws->s = take(r * W * act);
-    ws->mod[0] = take(r * 3 * W * act);
-    ws->mod[1] = take(r * 3 * W * act);
+    ws->mod = take(r * 3 * W * hd->L * act);
     ws->fm = (float*)take(r * 2 * W * 4);
     ws->h = (float*)take(r * W * 4);
     ws->u = take(r * W * 4);
@@ -128,8 +127,8 @@ hipError_t cond_embed(const csd_head* hd, const float* z, const HeadWs& ws, int6
 
 // One denoising step of one head is cut into phases p = 0 .. L+1, each a GEMM part followed
 // by an elementwise part (preceded once by s = SiLU(E_t + e)):
-//   G_0: mod_0                         E_0: block_pre(first)
-//   G_p: fc1_{p-1}, fc2_{p-1}, mod_p   E_p: block_pre(middle)        (1 <= p < L)
+//   G_0: mod of ALL blocks (one GEMM)  E_0: block_pre(first)
+//   G_p: fc1_{p-1}, fc2_{p-1}          E_p: block_pre(middle)        (1 <= p < L)
 //   G_L: fc1_{L-1}, fc2_{L-1}, fmod    E_L: block_pre(final)
 //   G_{L+1}: output projection         E_{L+1}: transition (by the caller)
 hipError_t phase_cond(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hipStream_t se) {
@@ -159,12 +158,20 @@ hipError_t phase_gemm(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hi
         g.bias = hd->fc2[l].b; g.C = ws.y; g.epi = EPI_BIAS;
         if ((e = gemm(hd, g, sg)) != hipSuccess) return e;
     }
-    // modulation of block p (p = L: the final one, kept in fp32 because it feeds eps_hat directly)
-    const Linear& ml = (p == L) ? hd->fmod : hd->mod[p];
-    g.A = ws.s; g.B = b16 ? (const void*)ml.w16 : (const void*)ml.w; g.bias = ml.b;
-    g.C = (p == L) ? (void*)ws.fm : ws.mod[p & 1]; g.N = ml.n_out; g.ldc = ml.n_out; g.epi = EPI_BIAS;
-    g.c_is_f32 = (p == L) ? 1 : 0;
-    return (p == L) ? gemm(hd, g, sg) : gemm_timed(hd, g, sg);
+    if (p == 0) {
+        // (shift, scale, gate) of all L blocks: [R,W] x [W, L*3W].  One launch instead of L: whole
+        // rounds of tiles even for a row chunk, and L-1 fewer dependent launches per step.
+        g.A = ws.s; g.B = b16 ? (const void*)hd->mod_all.w16 : (const void*)hd->mod_all.w; g.bias = hd->mod_all.b;
+        g.C = ws.mod; g.N = hd->mod_all.n_out; g.ldc = g.N; g.epi = EPI_BIAS; g.c_is_f32 = 0;
+        return gemm_timed(hd, g, sg);
+    }
+    if (p == L) {
+        // the final modulation, kept in fp32 because it feeds eps_hat directly
+        g.A = ws.s; g.B = b16 ? (const void*)hd->fmod.w16 : (const void*)hd->fmod.w; g.bias = hd->fmod.b;
+        g.C = ws.fm; g.N = hd->fmod.n_out; g.ldc = g.N; g.epi = EPI_BIAS; g.c_is_f32 = 1;
+        return gemm(hd, g, sg);
+    }
+    return hipSuccess;
 }
 
 // elementwise part of phases 0..L (residual or input projection, LN, modulation -> u)
@@ -177,9 +184,10 @@ hipError_t phase_elem(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hi
     bp.R = R; bp.W = W; bp.D = hd->D;
     bp.x = ws.x; bp.w_in = hd->in.w; bp.b_in = hd->in.b; bp.w_in_t = hd->d_in_t;
     bp.mode = (p == 0) ? 0 : (p == L ? 2 : 1);
-    bp.mod = (p == L) ? (const void*)ws.fm : (const void*)ws.mod[p & 1];
-    bp.ldm = (p == L) ? 2 * W : 3 * W;
-    if (p > 0) { bp.gate = (const char*)ws.mod[(p - 1) & 1] + (size_t)2 * W * asz; bp.ldg = 3 * W; }
+    const int ld_all = 3 * W * L;          // block l's (shift, scale, gate) sit at columns [l*3W, (l+1)*3W) of ws.mod
+    bp.mod = (p == L) ? (const void*)ws.fm : (const void*)((const char*)ws.mod + (size_t)p * 3 * W * asz);
+    bp.ldm = (p == L) ? 2 * W : ld_all;
+    if (p > 0) { bp.gate = (const char*)ws.mod + ((size_t)(p - 1) * 3 * W + 2 * W) * asz; bp.ldg = ld_all; }
     return launch_block_pre(bp, se);
 }
 
@@ -355,6 +363,8 @@ void csd_free_head(csd_head_t* h) {
     if (h->d_time_emb) (void)hipFree(h->d_time_emb);
     if (h->d_out_pad) (void)hipFree(h->d_out_pad);
     if (h->d_in_t) (void)hipFree(h->d_in_t);
+    if (h->d_mod_all) (void)hipFree(h->d_mod_all);
+    if (h->d_mod_all_bias) (void)hipFree(h->d_mod_all_bias);
     delete h;
 }
 
@@ -487,6 +497,22 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
         INIT_TRY(launch_f32_to_bf16_rows(h->out_pad.w, dst, 64, W, 2 * W, nullptr));
         INIT_TRY(launch_f32_to_bf16_rows(h->out_pad.w, dst + W, 64, W, 2 * W, nullptr));
         h->out_pad.w16 = dst;
+    }
+
+    // ---- the L modulation layers stacked into one [L*3W, W] matrix: they all read the same
+    // s = SiLU(E_t + e) and do not depend on the trajectory, so one GEMM per step serves them all
+    {
+        const size_t per = (size_t)3 * W * W, nb = (size_t)3 * W;
+        INIT_TRY(hipMalloc(&h->d_mod_all, (size_t)L * per * (b16 ? sizeof(bf16_t) : sizeof(float))));
+        INIT_TRY(hipMalloc((void**)&h->d_mod_all_bias, (size_t)L * nb * sizeof(float)));
+        for (int l = 0; l < L; ++l) {
+            if (b16) INIT_TRY(hipMemcpy((bf16_t*)h->d_mod_all + l * per, h->mod[l].w16, per * sizeof(bf16_t), hipMemcpyDeviceToDevice));
+            else INIT_TRY(hipMemcpy((float*)h->d_mod_all + l * per, h->mod[l].w, per * sizeof(float), hipMemcpyDeviceToDevice));
+            INIT_TRY(hipMemcpy(h->d_mod_all_bias + l * nb, h->mod[l].b, nb * sizeof(float), hipMemcpyDeviceToDevice));
+        }
+        h->mod_all.w = b16 ? nullptr : (const float*)h->d_mod_all;
+        h->mod_all.w16 = b16 ? (const bf16_t*)h->d_mod_all : nullptr;
+        h->mod_all.b = h->d_mod_all_bias; h->mod_all.n_out = L * 3 * W; h->mod_all.n_in = W;
     }
 
     // ---- time embedding table E_t[t], t = 1..T: sinusoidal features in double on the

@@ -42,6 +42,7 @@ struct Params {
     const bf16_t* gate; int ldg;
     int M, N, K;
     int tiles_m, tiles_n;
+    int panel;                  // > 0: an XCD walks its tiles in column panels of this many N-tiles
 };
 
 // s_waitcnt with only vmcnt set (expcnt and lgkmcnt left at "don't wait")
@@ -70,13 +71,24 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
     // ---- tile of this workgroup: ids sharing id%8 (one XCD) sweep n first, then m
-    int tile = blockIdx.x;
+    int tm, tn;
     {
+        int tile = blockIdx.x;
         const int total = p.tiles_m * p.tiles_n;
         const int per_xcd = total / 8;
-        if (per_xcd * 8 == total) tile = (tile % 8) * per_xcd + tile / 8;
+        const bool by_xcd = per_xcd * 8 == total;
+        if (by_xcd) tile = (tile % 8) * per_xcd + tile / 8;
+        tm = tile / p.tiles_n; tn = tile % p.tiles_n;
+        if (by_xcd && p.panel > 0 && per_xcd % p.tiles_n == 0) {
+            // very wide N (the stacked modulation layers): the XCD's rows x panel of N-tiles at a
+            // time, so that the weight panel in flight is shared by all its rows through L2 and
+            // its few A row-tiles stay there from panel to panel
+            const int rows = per_xcd / p.tiles_n, i = (int)blockIdx.x / 8;
+            const int per_panel = p.panel * rows, pn = i / per_panel, j = i % per_panel;
+            tm = ((int)blockIdx.x % 8) * rows + j / p.panel;
+            tn = pn * p.panel + j % p.panel;
+        }
     }
-    const int tm = tile / p.tiles_n, tn = tile % p.tiles_n;
     const int64_t m0 = (int64_t)tm * BM;
     const int n0 = tn * BN;
 
@@ -134,7 +146,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
         // under the MFMAs of step 3 - no wave ever waits at a slab boundary with an empty MFMA
         // pipe.  The requests for slab s+2 go out in two halves, after the barrier and in step 0
         // of the next slab, so that no wave sits long in the queue of the load unit.
-        static_assert(BK == 64 && NST == 2 && GPW % 2 == 0, "pipelined loop: two stages of 64");
+        static_assert(BK == 64 && NST == 2, "pipelined loop: two stages of 64");
         bf16x8 fa[2][FM], fb[2][FN];
         auto read_frags = [&](auto buf_c, int stage, int kk) {
             constexpr int buf = decltype(buf_c)::value;
@@ -180,19 +192,21 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
         };
         typedef std::integral_constant<int, 0> I0;
         typedef std::integral_constant<int, 1> I1;
-        typedef std::integral_constant<int, GPW / 2> IH;
+        constexpr int H1 = (GPW + 1) / 2, H2 = GPW - H1;      // the two halves of a slab's load requests
+        typedef std::integral_constant<int, H1> IH1;
+        typedef std::integral_constant<int, H2> IH2;
         typedef std::true_type RD;
         auto slab = [&](auto first_c, auto next1_c, auto next2_c, int s) {
             constexpr bool FIRST = decltype(first_c)::value, NEXT1 = decltype(next1_c)::value, NEXT2 = decltype(next2_c)::value;
             const int st = s & 1;
-            if constexpr (!FIRST && NEXT1) step(I0{}, RD{}, st, 1, IH{}, st ^ 1, (s + 1) * BK, GPW / 2);
+            if constexpr (!FIRST && NEXT1) step(I0{}, RD{}, st, 1, IH2{}, st ^ 1, (s + 1) * BK, H1);
             else step(I0{}, RD{}, st, 1, I0{}, 0, 0, 0);
             step(I1{}, RD{}, st, 2, I0{}, 0, 0, 0);
             step(I0{}, RD{}, st, 3, I0{}, 0, 0, 0);
             if constexpr (NEXT1) wait_vmcnt<0>();
             wait_lds_reads();
             __builtin_amdgcn_s_barrier();
-            if constexpr (NEXT2) step(I1{}, RD{}, st ^ 1, 0, IH{}, st, (s + 2) * BK, 0);
+            if constexpr (NEXT2) step(I1{}, RD{}, st ^ 1, 0, IH1{}, st, (s + 2) * BK, 0);
             else if constexpr (NEXT1) step(I1{}, RD{}, st ^ 1, 0, I0{}, 0, 0, 0);
             else step(I1{}, std::false_type{}, 0, 0, I0{}, 0, 0, 0);
         };
@@ -310,6 +324,10 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     p.C = g.C; p.ldc = g.ldc; p.gate = (const bf16_t*)g.gate; p.ldg = g.ldg;
     p.M = g.M; p.N = g.N; p.K = g.K;
     p.tiles_m = (g.M + BM - 1) / BM; p.tiles_n = g.N / BN;
+    p.panel = 0;
+    if (p.tiles_n > 16)
+        for (int d = 16; d >= 8; --d)
+            if (p.tiles_n % d == 0) { p.panel = d; break; }
     const size_t smem = (size_t)NST * (BM + BN) * BK * 2;
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WM * WN * 64);
 #define CSD_LAUNCH(EPI, F32)                                                                                   \
@@ -352,7 +370,10 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
         // large problems: 256-row tiles, 256 (or 192) columns wide
         // (192 wins for one GEMM alone on the chip, e.g. 16384x768x768: 28 vs 34 us, but loses 5 % on
         // the whole path, where several chains share the chip; it is used only where 256 does not divide N)
-        if (g.M >= 2048 && g.N % 256 == 0) variant = 9;
+        static int pref192 = -1;
+        if (pref192 < 0) { const char* e = getenv("CSD_GEMM_192"); pref192 = (e && *e == '1') ? 1 : 0; }
+        if (pref192 && g.M >= 2048 && g.N % 768 == 0 && g.N % 1024 != 0) variant = 8;
+        else if (g.M >= 2048 && g.N % 256 == 0) variant = 9;
         else if (g.M >= 2048 && g.N % 192 == 0) variant = 8;
         // below that the launch is latency-bound and wants many small workgroups: the 64x64 tile beats
         // 128x128 at every M measured (one head pass at 256 / 1024 rows: 263 / 290 us against 343 / 366),
@@ -372,7 +393,8 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
         case 6: return launch_cfg<256, 128, 2, 2, 64, 2>(g, st);    // same tile, BK 64, 96 KiB LDS
         case 9: if (g.K >= 256) return launch_cfg<256, 256, 2, 4, 64, 2, true>(g, st);   // 8 waves, software-pipelined main loop
                 return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);
-        case 8: return launch_cfg<256, 192, 4, 2, 64, 2>(g, st);    // 8 waves, 64x96 per wave: N = 3 * 2^k widths
+        case 8: if (g.K >= 256) return launch_cfg<256, 192, 4, 2, 64, 2, true>(g, st);
+                return launch_cfg<256, 192, 4, 2, 64, 2>(g, st);    // 8 waves, 64x96 per wave: N = 3 * 2^k widths
         default: return launch_cfg<64, 64, 2, 2, 64, 2>(g, st);     // 4 waves, 32x32 per wave
     }
 }

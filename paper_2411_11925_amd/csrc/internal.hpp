@@ -57,6 +57,9 @@ struct csd_head {
     float* d_out_pad = nullptr;          // storage of out_pad (fp32 w, b)
     float* d_in_t = nullptr;             // input projection transposed to [D, W]
     std::vector<csd::Linear> mod, fc1, fc2;
+    csd::Linear mod_all;                 // the L modulation layers stacked: [L*3W, W], one GEMM per step
+    void* d_mod_all = nullptr;           // its weights (bf16 or fp32 by gemm dtype) ...
+    float* d_mod_all_bias = nullptr;     // ... and bias [L*3W]
     std::vector<csd::StepCoef> coef;     // [T+1], entry 0 unused
     std::vector<float> skip_sqrt;        // [T+1]: eps_skip_gain * sqrt(1 - abar_t)
     double ref_log_sigma;                // sum_{t=2..T} D/2 * lmid_t in double

@@ -231,7 +231,9 @@ def _bf16(a):
                                    (2048 + 37, 768, 256), (4096, 1024, 1024),
                                    # more tiles than CUs (several tiles per persistent workgroup), ragged
                                    # last row of tiles, tile counts that do and do not divide by 8
-                                   (8192 + 100, 3072, 512), (16384, 2304, 192)])
+                                   (8192 + 100, 3072, 512), (16384, 2304, 192),
+                                   # very wide N: column-panel tile order (18 N-tiles: panels of 9; 1 and 2 rows per XCD)
+                                   (2048, 4608, 256), (4096, 4608, 320)])
 def test_gemm_bf16_all_epilogues(B, M, N, K):
     rng = np.random.default_rng(M + N + K)
     A = S.bf16_round(rng.normal(size=(M, K)).astype(np.float32))
