@@ -55,18 +55,40 @@ size_t param_count(const csd_head_cfg_t* c) {
 
 size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// device buffers of one head for R rows, carved from the caller's workspace
+// device buffers of one head for R rows, carved from the caller's workspace.  s, mod and fm do
+// not depend on the trajectory (only on the step and the conditioning vector), so they are
+// computed for `tb` consecutive denoising steps at once: [tb, R, .].  With few rows that turns
+// the largest GEMMs of a step, which would be launch- and latency-bound at M = R, into GEMMs
+// over tb*R rows; with many rows tb is 1.
 struct HeadWs {
     float* e; void* s; void* mod; float* fm; float* h; void* u; void* a; void* y; float* o; float* x; float* acc;
+    int tb;
 };
 
-size_t head_ws_bytes(const csd_head* hd, int64_t R) {
+constexpr size_t BATCH_BUDGET = (size_t)256 << 20;     // bytes of s + mod + fm a batch of steps may take
+
+size_t batched_bytes_per_row(const csd_head* hd) {
+    const size_t W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
+    return W * act + 3 * W * hd->L * act + 2 * W * 4;
+}
+
+// steps per batch for a call of R rows (row chunks of the call use the same value)
+int steps_per_batch(const csd_head* hd, int64_t R) {
+    if (R <= 0) return 1;
+    const size_t per_step = (size_t)R * batched_bytes_per_row(hd);
+    size_t tb = BATCH_BUDGET / per_step;
+    if (tb < 1) tb = 1;
+    if (tb > (size_t)hd->T) tb = (size_t)hd->T;
+    return (int)tb;
+}
+
+size_t head_ws_bytes(const csd_head* hd, int64_t R, int tb) {
     const size_t r = (size_t)R, W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
     size_t n = 0;
     n += align_up(r * W * 4, 256);          // e
-    n += align_up(r * W * act, 256);        // s
-    n += align_up(r * 3 * W * hd->L * act, 256);  // mod: (shift, scale, gate) of all L blocks, [R, L*3W]
-    n += align_up(r * 2 * W * 4, 256);      // fm (fp32 in both modes)
+    n += align_up(tb * r * W * act, 256);   // s
+    n += align_up(tb * r * 3 * W * hd->L * act, 256);  // mod: (shift, scale, gate) of all L blocks, [tb, R, L*3W]
+    n += align_up(tb * r * 2 * W * 4, 256); // fm (fp32 in both modes)
     n += align_up(r * W * 4, 256);          // h
     n += align_up(r * W * 4, 256);          // u (fp32, bf16, or the [hi|lo] bf16 pair of the last layer)
     n += 2 * align_up(r * W * act, 256);    // a, y
@@ -76,13 +98,14 @@ size_t head_ws_bytes(const csd_head* hd, int64_t R) {
     return n;
 }
 
-char* carve(const csd_head* hd, int64_t R, char* p, HeadWs* ws) {
+char* carve(const csd_head* hd, int64_t R, int tb, char* p, HeadWs* ws) {
     const size_t r = (size_t)R, W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
     auto take = [&](size_t bytes) { char* q = p; p += align_up(bytes, 256); return q; };
+    ws->tb = tb;
     ws->e = (float*)take(r * W * 4);
-    ws->s = take(r * W * act);
-    ws->mod = take(r * 3 * W * hd->L * act);
-    ws->fm = (float*)take(r * 2 * W * 4);
+    ws->s = take(tb * r * W * act);
+    ws->mod = take(tb * r * 3 * W * hd->L * act);
+    ws->fm = (float*)take(tb * r * 2 * W * 4);
     ws->h = (float*)take(r * W * 4);
     ws->u = take(r * W * 4);
     ws->a = take(r * W * act);
@@ -125,17 +148,29 @@ hipError_t cond_embed(const csd_head* hd, const float* z, const HeadWs& ws, int6
     return launch_gemm_f32(g, st);
 }
 
-// One denoising step of one head is cut into phases p = 0 .. L+1, each a GEMM part followed
-// by an elementwise part (preceded once by s = SiLU(E_t + e)):
-//   G_0: mod of ALL blocks (one GEMM)  E_0: block_pre(first)
-//   G_p: fc1_{p-1}, fc2_{p-1}          E_p: block_pre(middle)        (1 <= p < L)
-//   G_L: fc1_{L-1}, fc2_{L-1}, fmod    E_L: block_pre(final)
-//   G_{L+1}: output projection         E_{L+1}: transition (by the caller)
-hipError_t phase_cond(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hipStream_t se) {
-    const int act = hd->cfg.gemm_dtype == CSD_BF16 ? ACT_BF16 : ACT_F32;
-    return launch_cond_silu(ws.e, hd->d_time_emb + (size_t)t * hd->W, ws.s, act, R, hd->W, se);
+// Before the first step of a batch: for the nb steps t_first, t_first-1, ..: s = SiLU(E_t + e),
+// the (shift, scale, gate) of all L blocks - [nb*R, W] x [W, L*3W], one GEMM - and the final
+// modulation (fp32, because it feeds eps_hat directly).
+hipError_t batch_stage(const csd_head* hd, const HeadWs& ws, int t_first, int nb, int64_t R, hipStream_t st) {
+    const int W = hd->W;
+    const bool b16 = hd->cfg.gemm_dtype == CSD_BF16;
+    hipError_t e = launch_cond_silu(ws.e, hd->d_time_emb + (size_t)t_first * W, nb, ws.s, b16 ? ACT_BF16 : ACT_F32, R, W, st);
+    if (e != hipSuccess) return e;
+    GemmArgs g{};
+    g.M = (int)(R * nb); g.K = W; g.lda = W; g.A = ws.s; g.epi = EPI_BIAS;
+    g.B = b16 ? (const void*)hd->mod_all.w16 : (const void*)hd->mod_all.w; g.bias = hd->mod_all.b;
+    g.C = ws.mod; g.N = hd->mod_all.n_out; g.ldc = g.N; g.c_is_f32 = 0;
+    if ((e = gemm_timed(hd, g, st)) != hipSuccess) return e;
+    g.B = b16 ? (const void*)hd->fmod.w16 : (const void*)hd->fmod.w; g.bias = hd->fmod.b;
+    g.C = ws.fm; g.N = hd->fmod.n_out; g.ldc = g.N; g.c_is_f32 = 1;
+    return gemm(hd, g, st);
 }
 
+// The trajectory-dependent part of one denoising step, in phases p = 0 .. L+1:
+//   p = 0:       block_pre(first)
+//   1 <= p <= L: fc1_{p-1}, fc2_{p-1}, then block_pre(middle; final for p = L)
+//   p = L+1:     output projection (the transition follows, by the caller)
+// k = index of the step within its batch (selects the slice of s / mod / fm).
 hipError_t phase_gemm(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hipStream_t sg) {
     const int W = hd->W, L = hd->L;
     const bool b16 = hd->cfg.gemm_dtype == CSD_BF16;
@@ -158,24 +193,11 @@ hipError_t phase_gemm(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hi
         g.bias = hd->fc2[l].b; g.C = ws.y; g.epi = EPI_BIAS;
         if ((e = gemm(hd, g, sg)) != hipSuccess) return e;
     }
-    if (p == 0) {
-        // (shift, scale, gate) of all L blocks: [R,W] x [W, L*3W].  One launch instead of L: whole
-        // rounds of tiles even for a row chunk, and L-1 fewer dependent launches per step.
-        g.A = ws.s; g.B = b16 ? (const void*)hd->mod_all.w16 : (const void*)hd->mod_all.w; g.bias = hd->mod_all.b;
-        g.C = ws.mod; g.N = hd->mod_all.n_out; g.ldc = g.N; g.epi = EPI_BIAS; g.c_is_f32 = 0;
-        return gemm_timed(hd, g, sg);
-    }
-    if (p == L) {
-        // the final modulation, kept in fp32 because it feeds eps_hat directly
-        g.A = ws.s; g.B = b16 ? (const void*)hd->fmod.w16 : (const void*)hd->fmod.w; g.bias = hd->fmod.b;
-        g.C = ws.fm; g.N = hd->fmod.n_out; g.ldc = g.N; g.epi = EPI_BIAS; g.c_is_f32 = 1;
-        return gemm(hd, g, sg);
-    }
     return hipSuccess;
 }
 
 // elementwise part of phases 0..L (residual or input projection, LN, modulation -> u)
-hipError_t phase_elem(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hipStream_t se) {
+hipError_t phase_elem(const csd_head* hd, const HeadWs& ws, int p, int k, int64_t R, hipStream_t se) {
     const int W = hd->W, L = hd->L;
     const bool b16 = hd->cfg.gemm_dtype == CSD_BF16;
     const size_t asz = b16 ? 2 : 4;
@@ -184,20 +206,20 @@ hipError_t phase_elem(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hi
     bp.R = R; bp.W = W; bp.D = hd->D;
     bp.x = ws.x; bp.w_in = hd->in.w; bp.b_in = hd->in.b; bp.w_in_t = hd->d_in_t;
     bp.mode = (p == 0) ? 0 : (p == L ? 2 : 1);
-    const int ld_all = 3 * W * L;          // block l's (shift, scale, gate) sit at columns [l*3W, (l+1)*3W) of ws.mod
-    bp.mod = (p == L) ? (const void*)ws.fm : (const void*)((const char*)ws.mod + (size_t)p * 3 * W * asz);
+    const int ld_all = 3 * W * L;          // block l's (shift, scale, gate) sit at columns [l*3W, (l+1)*3W) of a mod row
+    const char* mod_k = (const char*)ws.mod + (size_t)k * R * ld_all * asz;        // step k of the batch
+    bp.mod = (p == L) ? (const void*)(ws.fm + (size_t)k * R * 2 * W) : (const void*)(mod_k + (size_t)p * 3 * W * asz);
     bp.ldm = (p == L) ? 2 * W : ld_all;
-    if (p > 0) { bp.gate = (const char*)ws.mod + ((size_t)(p - 1) * 3 * W + 2 * W) * asz; bp.ldg = ld_all; }
+    if (p > 0) { bp.gate = mod_k + ((size_t)(p - 1) * 3 * W + 2 * W) * asz; bp.ldg = ld_all; }
     return launch_block_pre(bp, se);
 }
 
-// whole step on one stream (csd_head_eval)
-hipError_t head_body(const csd_head* hd, const HeadWs& ws, int t, int64_t R, hipStream_t st) {
+// the trajectory-dependent part of a step on one stream
+hipError_t head_body(const csd_head* hd, const HeadWs& ws, int k, int64_t R, hipStream_t st) {
     hipError_t e;
-    if ((e = phase_cond(hd, ws, t, R, st)) != hipSuccess) return e;
     for (int p = 0; p <= hd->L + 1; ++p) {
         if ((e = phase_gemm(hd, ws, p, R, st)) != hipSuccess) return e;
-        if (p <= hd->L && (e = phase_elem(hd, ws, p, R, st)) != hipSuccess) return e;
+        if (p <= hd->L && (e = phase_elem(hd, ws, p, k, R, st)) != hipSuccess) return e;
     }
     return hipSuccess;
 }
@@ -295,7 +317,9 @@ int run_chains(Chain* chains, int n_chains, uint64_t seed, float tau, hipStream_
     for (int t = T; t >= 1; --t) {
         for (int i = 0; i < n_chains; ++i) {
             Chain& ch = chains[i];
-            HIP_TRY(head_body(ch.hd, ch.ws, t, ch.n, ch.s));
+            const int k = (T - t) % ch.ws.tb;
+            if (k == 0) HIP_TRY(batch_stage(ch.hd, ch.ws, t, t < ch.ws.tb ? t : ch.ws.tb, ch.n, ch.s));
+            HIP_TRY(head_body(ch.hd, ch.ws, k, ch.n, ch.s));
             TransArgs f = trans_args(ch.hd, ch.ws, t, ch.n);
             f.seed = seed; f.row_offset = ch.row_offset; f.tau = tau;
             f.row_stride = ch.row_stride; f.row_shift = ch.row_shift; f.rng_stream = ch.rng_stream;
@@ -336,7 +360,7 @@ int run_single_head(const csd_head* hd, const float* z, int64_t n, uint64_t seed
         ch.rng_stream = rng_stream; ch.is_target = is_target;
         ch.summary = summary ? summary + r0 * row_stride * (5 * hd->D + 1) : nullptr;
         ch.tokens = tokens ? tokens + r0 * hd->D : nullptr;
-        wp = carve(hd, m, wp, &ch.ws);
+        wp = carve(hd, m, steps_per_batch(hd, n), wp, &ch.ws);
     }
     *n_chains_out = n_chunks;
     return run_chains(chains, n_chunks, seed, tau, st, side);
@@ -548,11 +572,11 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
 
 size_t csd_workspace_bytes(const csd_head_t* draft, const csd_head_t* target, int64_t n_rows) {
     if (n_rows < 0 || (!draft && !target)) return 0;
-    // room for up to 4 row chunks, each rounded up to 256 rows (see csd_denoise_lockstep)
-    const int64_t padded = n_rows + 4 * 256;
+    // the row chunks of a call (see plan_chunks) add up to n_rows; every buffer of every chunk is
+    // aligned to 256 bytes, which the slack covers (up to 4 chunks x 11 buffers)
     size_t n = 256;
-    if (draft) n += head_ws_bytes(draft, padded) + 4 * 16 * 256;
-    if (target) n += head_ws_bytes(target, padded) + 4 * 16 * 256;
+    if (draft) n += head_ws_bytes(draft, n_rows, steps_per_batch(draft, n_rows)) + 4 * 16 * 256;
+    if (target) n += head_ws_bytes(target, n_rows, steps_per_batch(target, n_rows)) + 4 * 16 * 256;
     return n;
 }
 
@@ -590,7 +614,7 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, cons
             ch.hd = which ? target : draft; ch.n = n; ch.z = (which ? z_p : z_q) + r0 * ch.hd->C;
             ch.row_offset = row_offset + (uint64_t)r0; ch.row_stride = 1; ch.row_shift = 0; ch.rng_stream = CSD_STREAM_TRAJ;
             ch.summary = summary + r0 * (5 * D + 1); ch.is_target = which; ch.tokens = nullptr;
-            wp_ = carve(ch.hd, n, wp_, &ch.ws);
+            wp_ = carve(ch.hd, n, steps_per_batch(ch.hd, R), wp_, &ch.ws);
         }
     }
     int rc = run_chains(chains, n_chains, seed, temperature, st, side);
@@ -694,10 +718,11 @@ int csd_head_eval(const csd_head_t* head, const float* x, const float* z, int32_
                     csd_workspace_bytes(head, nullptr, n_rows));
     hipStream_t st = (hipStream_t)hip_stream;
     HeadWs ws;
-    carve(head, n_rows, (char*)workspace, &ws);
+    carve(head, n_rows, steps_per_batch(head, n_rows), (char*)workspace, &ws);
     HIP_TRY(hipMemcpyAsync(ws.x, x, (size_t)n_rows * head->D * sizeof(float), hipMemcpyDeviceToDevice, st));
     HIP_TRY(cond_embed(head, z, ws, n_rows, st));
-    HIP_TRY(head_body(head, ws, t, n_rows, st));
+    HIP_TRY(batch_stage(head, ws, t, 1, n_rows, st));
+    HIP_TRY(head_body(head, ws, 0, n_rows, st));
     TransArgs f = trans_args(head, ws, t, n_rows);
     f.raw_out = out; f.skip_coef = head->skip_sqrt[t];
     HIP_TRY(launch_transition(f, st));

@@ -25,23 +25,27 @@ __device__ __forceinline__ float wave_sum(float v) {
 // ---------------------------------------------------------------- s = silu(E_t + e)
 template <typename TAct>
 __global__ void k_cond_silu(const float* __restrict__ e, const float* __restrict__ temb, TAct* __restrict__ s,
-                            size_t n, int W) {
+                            size_t n_one, int n_steps, int W) {
+    // s[k, r, :] = silu(e[r, :] + E[t_first - k, :]) for the steps k = 0 .. n_steps-1 of a batch;
+    // temb points at row t_first of the table, earlier steps are the rows before it
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x, n = n_one * (size_t)n_steps;
     for (; i < n; i += stride) {
-        const int w = (int)(i % (size_t)W);
-        act_store<TAct>(s, i, silu_f(e[i] + temb[w]));
+        const size_t k = i / n_one, j = i - k * n_one;
+        const int w = (int)(j % (size_t)W);
+        act_store<TAct>(s, i, silu_f(e[j] + temb[w - (ptrdiff_t)k * W]));
     }
 }
 
-hipError_t launch_cond_silu(const float* e, const float* temb, void* s, int act, int64_t R, int W, hipStream_t st) {
-    const size_t n = (size_t)R * W;
+hipError_t launch_cond_silu(const float* e, const float* temb_first, int n_steps, void* s, int act, int64_t R, int W,
+                            hipStream_t st) {
+    const size_t n_one = (size_t)R * W, n = n_one * (size_t)n_steps;
     if (n == 0) return hipSuccess;
     const int threads = 256;
     const size_t want = (n + threads - 1) / threads;
     const int blocks = (int)(want < 16384 ? want : 16384);
-    if (act == ACT_BF16) hipLaunchKernelGGL(k_cond_silu<bf16_t>, dim3(blocks), dim3(threads), 0, st, e, temb, (bf16_t*)s, n, W);
-    else hipLaunchKernelGGL(k_cond_silu<float>, dim3(blocks), dim3(threads), 0, st, e, temb, (float*)s, n, W);
+    if (act == ACT_BF16) hipLaunchKernelGGL(k_cond_silu<bf16_t>, dim3(blocks), dim3(threads), 0, st, e, temb_first, (bf16_t*)s, n_one, n_steps, W);
+    else hipLaunchKernelGGL(k_cond_silu<float>, dim3(blocks), dim3(threads), 0, st, e, temb_first, (float*)s, n_one, n_steps, W);
     return hipGetLastError();
 }
 

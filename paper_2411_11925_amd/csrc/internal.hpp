@@ -92,8 +92,9 @@ struct GemmArgs {
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st);
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st);
 
-// s = silu(E_t + e)
-hipError_t launch_cond_silu(const float* e, const float* time_emb_t, void* s, int act, int64_t R, int W, hipStream_t st);
+// s[k] = silu(E_{t-k} + e) for k = 0 .. n_steps-1 (a batch of consecutive denoising steps); time_emb_t = row t of the table
+hipError_t launch_cond_silu(const float* e, const float* time_emb_t, int n_steps, void* s, int act, int64_t R, int W,
+                            hipStream_t st);
 // start of a block: residual of the previous block (or the input projection), LN, modulation
 struct BlockPreArgs {
     int mode;                  // 0 first block, 1 middle, 2 after the last block (see elementwise.hip)
