@@ -400,3 +400,44 @@ def test_table_schedule_and_unequal_schedules_f32(B):
         B.csd_init_head(mk(np.concatenate([[1.0], np.full(T, 0.5)])), db)
     for h in (hq_c, hp_c, hq_t, hp_t, hq_l):
         h.free()
+
+
+# ------------------------------------------------------------ the stated limits ----
+@pytest.mark.parametrize("shape,T,R,dtype", [
+    (S.HeadShape(4, 8, 4096, 1), 2, 70, "f32"),        # widest head, smallest token and cond dims
+    (S.HeadShape(4, 8, 4096, 1), 2, 300, "bf16"),
+    (S.HeadShape(8, 16384, 64, 2), 3, 33, "f32"),      # largest cond dim, narrowest head
+    (S.HeadShape(16, 64, 64, 64), 2, 40, "f32"),       # deepest head
+    (S.HeadShape(16, 24, 320, 3), 5, 129, "bf16")])    # width that is no multiple of 256 or 192
+def test_heads_at_the_limits_of_the_interface(B, shape, T, R, dtype):
+    blob = S.head_weights(shape, 31, out_scale=0.3, bias_std=0.1)
+    if dtype == "bf16":
+        blob = S.bf16_round(blob)
+    oh = O.Head(O.HeadCfg(shape.token_dim, shape.cond_dim, shape.width, shape.n_blocks, T, eps_skip_gain=1.0), blob)
+    dh = B.csd_init_head(B.make_cfg(shape.token_dim, shape.cond_dim, shape.width, shape.n_blocks, T,
+                                    B.CSD_BF16 if dtype == "bf16" else B.CSD_F32, eps_skip_gain=1.0), blob)
+    rng = np.random.default_rng(8)
+    z = rng.normal(size=(R, shape.cond_dim)).astype(np.float32)
+    want = O.sample(oh, z, 77, 5, 1.0)
+    got = B.csd_sample(dh, _t(z), 77, 5).cpu().numpy()
+    assert H.rel_err(got, want) < (1.5 * H.BF16_TOL if dtype == "bf16" else H.F32_TOL)
+    dh.free()
+
+
+def test_longest_schedule_f32(B):
+    """T = 4096 denoising steps (the interface's limit) with a tiny head: the step indexing,
+    the noise slots and the log Sigma accumulation hold over the whole range."""
+    shape, T, G, gamma = S.HeadShape(4, 8, 64, 1), 4096, 6, 2
+    tb = S.head_weights(shape, 41, out_scale=0.02, bias_std=0.05)
+    db = S.perturbed_copy(tb, shape, 42, 0.05, 0.02)
+    ocfg = O.HeadCfg(4, 8, 64, 1, T, eps_skip_gain=1.0)
+    oq, op = O.Head(ocfg, db), O.Head(ocfg, tb)
+    mk = lambda: B.make_cfg(4, 8, 64, 1, T, B.CSD_F32, eps_skip_gain=1.0)
+    dq, dp = B.csd_init_head(mk(), db), B.csd_init_head(mk(), tb)
+    zq, zp = S.cond_vectors(G * gamma, 8, 4, add_std=0.1)
+    want, _ = O.denoise_lockstep(oq, op, zq, zp, seed=3, row_offset=2 ** 40)
+    got = B.csd_denoise_lockstep(dq, dp, _t(zq), _t(zp), G, gamma, 3, 2 ** 40).cpu().numpy()
+    D = 4
+    assert H.rel_err(got[:, 4 * D:5 * D], want[:, 4 * D:5 * D]) < 3 * H.F32_TOL      # 4096 fp32 steps
+    assert np.max(np.abs(got[:, -1] - want[:, -1])) < 1e-3 * max(1.0, np.abs(want[:, -1]).max())
+    dq.free(); dp.free()
