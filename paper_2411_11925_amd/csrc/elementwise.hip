@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void k_block_pre(BlockPreArgs a) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             const int j = (c * 64 + lane) * 4;
-            store4<float>(hrow + j, hv[c]);
+            if (MODE != PRE_FINAL) store4<float>(hrow + j, hv[c]);     // nobody reads h after the last block
             emit(j, hv[c], 4, mean, rstd);
         }
     } else {
@@ -165,64 +165,81 @@ __global__ __launch_bounds__(256) void k_block_pre(BlockPreArgs a) {
 
 // First block, fast path: h = W_in x + b_in for FOUR rows per wave, so that each 16-byte
 // piece of the (transposed, [D][W]) input weights is loaded once per four rows; then the
-// same LN + modulation as above, row by row.
-template <typename TAct, int D, int NCH>
+// same LN + modulation as above.  The row is streamed in chunks of 256 columns (h is written
+// in the first sweep and read back - from L2 - for the centred variance and for u), which
+// keeps the kernel at a few dozen registers: it is bandwidth-bound and wants many waves.
+template <typename TAct, int D>
 __global__ __launch_bounds__(256) void k_block_first(BlockPreArgs a) {
     constexpr int RPW = 4;
     const int lane = threadIdx.x & 63;
     const int64_t r0 = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * RPW;
     if (r0 >= a.R) return;
-    const int W = a.W;
+    const int W = a.W, nch = W / 256;
+    const float* __restrict__ w_src = a.w_in;
     float xr[RPW][D];
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
         const int64_t r = (r0 + rr < a.R) ? r0 + rr : a.R - 1;
 #pragma unroll
-        for (int d = 0; d < D; ++d) xr[rr][d] = a.x[r * D + d];
+        for (int d = 0; d < D; ++d)      // the same value in every lane: keep it in a scalar register
+            xr[rr][d] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(a.x[r * D + d])));
     }
-    float hv[RPW][NCH][4];
+    float s[RPW], mean[RPW], q[RPW], rstd[RPW];
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
+    for (int rr = 0; rr < RPW; ++rr) { s[rr] = 0.f; q[rr] = 0.f; }
+#pragma unroll 1
+    for (int c = 0; c < nch; ++c) {
         const int j = (c * 64 + lane) * 4;
-        float b4[4];
+        float hv[RPW][4], b4[4];
         load4<float>(a.b_in + j, b4);
 #pragma unroll
         for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) hv[rr][c][e] = b4[e];
+            for (int e = 0; e < 4; ++e) hv[rr][e] = b4[e];
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             float w4[4];
-            load4<float>(a.w_in + (size_t)d * W + j, w4);
+            load4<float>(w_src + (size_t)d * W + j, w4);
 #pragma unroll
             for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) hv[rr][c][e] = fmaf(w4[e], xr[rr][d], hv[rr][c][e]);
+                for (int e = 0; e < 4; ++e) hv[rr][e] = fmaf(w4[e], xr[rr][d], hv[rr][e]);
+        }
+#pragma unroll
+        for (int rr = 0; rr < RPW; ++rr) {
+            s[rr] += (hv[rr][0] + hv[rr][1]) + (hv[rr][2] + hv[rr][3]);
+            if (r0 + rr < a.R) store4<float>(a.h + (r0 + rr) * W + j, hv[rr]);
         }
     }
 #pragma unroll
-    for (int rr = 0; rr < RPW; ++rr) {
-        const int64_t r = r0 + rr;
-        if (r >= a.R) break;
-        float s = 0.f;
+    for (int rr = 0; rr < RPW; ++rr) mean[rr] = wave_sum(s[rr]) / (float)W;
+#pragma unroll 1
+    for (int c = 0; c < nch; ++c) {
+        const int j = (c * 64 + lane) * 4;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) s += (hv[rr][c][0] + hv[rr][c][1]) + (hv[rr][c][2] + hv[rr][c][3]);
-        const float mean = wave_sum(s) / (float)W;
-        float q = 0.f;
+        for (int rr = 0; rr < RPW; ++rr) {
+            if (r0 + rr >= a.R) continue;
+            float hv[4];
+            load4<float>(a.h + (r0 + rr) * W + j, hv);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c)
+            for (int e = 0; e < 4; ++e) { const float d = hv[e] - mean[rr]; q[rr] = fmaf(d, d, q[rr]); }
+        }
+    }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { const float d = hv[rr][c][e] - mean; q = fmaf(d, d, q); }
-        const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)W + a.ln_eps);
-        const TAct* mrow = (const TAct*)a.mod + r * (size_t)a.ldm;
+    for (int rr = 0; rr < RPW; ++rr) rstd[rr] = 1.0f / sqrtf(wave_sum(q[rr]) / (float)W + a.ln_eps);
+#pragma unroll 1
+    for (int c = 0; c < nch; ++c) {
+        const int j = (c * 64 + lane) * 4;
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            const int j = (c * 64 + lane) * 4;
-            float sh[4], sc[4], uv[4];
+        for (int rr = 0; rr < RPW; ++rr) {
+            const int64_t r = r0 + rr;
+            if (r >= a.R) continue;
+            const TAct* mrow = (const TAct*)a.mod + r * (size_t)a.ldm;
+            float hv[4], sh[4], sc[4], uv[4];
+            load4<float>(a.h + r * W + j, hv);
             load4<TAct>(mrow + j, sh); load4<TAct>(mrow + W + j, sc);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) uv[e] = fmaf((hv[rr][c][e] - mean) * rstd, 1.0f + sc[e], sh[e]);
-            store4<float>(a.h + r * W + j, hv[rr][c]);
+            for (int e = 0; e < 4; ++e) uv[e] = fmaf((hv[e] - mean[rr]) * rstd[rr], 1.0f + sc[e], sh[e]);
             store4<TAct>((TAct*)a.u + r * (size_t)W + j, uv);
         }
     }
@@ -234,13 +251,8 @@ static bool launch_block_first(const BlockPreArgs& a, hipStream_t st) {
     BlockPreArgs b = a;
     b.w_in = a.w_in_t;
     dim3 grid((unsigned)((a.R + 15) / 16)), block(256);
-    switch (a.W / 256) {
-        case 2: hipLaunchKernelGGL((k_block_first<TAct, D, 2>), grid, block, 0, st, b); return true;
-        case 3: hipLaunchKernelGGL((k_block_first<TAct, D, 3>), grid, block, 0, st, b); return true;
-        case 4: hipLaunchKernelGGL((k_block_first<TAct, D, 4>), grid, block, 0, st, b); return true;
-        case 5: hipLaunchKernelGGL((k_block_first<TAct, D, 5>), grid, block, 0, st, b); return true;
-        default: return false;
-    }
+    hipLaunchKernelGGL((k_block_first<TAct, D>), grid, block, 0, st, b);
+    return true;
 }
 
 template <typename TAct, int MODE, int D>
