@@ -275,16 +275,21 @@ int csd_gemm_bf16(const void* A, const void* B, const float* bias, int64_t M, in
                   int32_t epilogue, int32_t out_f32, void* C, const void* gate, void* hip_stream);
 
 /*
- * Timing of the dominant kernel (the modulation GEMM of csd_denoise_lockstep).
+ * Timing of the dominant kernel (the modulation GEMM of the denoising calls).
  * While enabled, every launch of that kernel is bracketed by two hipEvents on its
- * launch stream (up to `max_launches`; later launches run untimed).
+ * launch stream (up to `max_launches`; later launches run untimed), and the bf16
+ * kernel records the times its first workgroup starts and its last one ends.
  * csd_profile_read waits for the recorded events and returns the sum of the
- * kernel durations in milliseconds, the number of launches timed and the sum of
- * their algorithmic flops (2*M*N*K each); it then clears the record.
+ * event-to-event durations in milliseconds, the number of launches timed, the
+ * sum of their algorithmic flops (2*M*N*K each) and, if ms_sum_on_device is not
+ * NULL, the sum of the first-start-to-last-end spans (0 if not available: fp32
+ * kernels); it then clears the record.  When several chains share the chip both
+ * figures include the time the kernel's workgroups share the compute units with
+ * the other chains' kernels (measured: the two agree within a few percent).
  * csd_profile_enable(0) stops recording and frees the events.
  */
 int csd_profile_enable(int32_t max_launches);
-int csd_profile_read(double* ms_sum, int64_t* launches, double* flops_sum);
+int csd_profile_read(double* ms_sum, int64_t* launches, double* flops_sum, double* ms_sum_on_device);
 
 /* Message of the last failing call on this thread ("" if none). */
 const char* csd_last_error(void);

@@ -91,7 +91,7 @@ _lib.csd_gemm_bf16.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int32, c
 _lib.csd_profile_enable.restype = c_int
 _lib.csd_profile_enable.argtypes = [c_int32]
 _lib.csd_profile_read.restype = c_int
-_lib.csd_profile_read.argtypes = [POINTER(c_double), POINTER(c_int64), POINTER(c_double)]
+_lib.csd_profile_read.argtypes = [POINTER(c_double), POINTER(c_int64), POINTER(c_double), POINTER(c_double)]
 
 
 class CsdError(RuntimeError):
@@ -333,7 +333,8 @@ def csd_profile_enable(max_launches: int):
 
 
 def csd_profile_read():
-    """(sum of kernel milliseconds, launches timed, sum of algorithmic flops)."""
-    ms, n, fl = c_double(), c_int64(), c_double()
-    _check(_lib.csd_profile_read(byref(ms), byref(n), byref(fl)))
-    return ms.value, n.value, fl.value
+    """(sum of event-to-event milliseconds, launches timed, sum of algorithmic flops,
+    sum of first-workgroup-start to last-workgroup-end milliseconds or 0.0)."""
+    ms, n, fl, dev = c_double(), c_int64(), c_double(), c_double()
+    _check(_lib.csd_profile_read(byref(ms), byref(n), byref(fl), byref(dev)))
+    return ms.value, n.value, fl.value, dev.value

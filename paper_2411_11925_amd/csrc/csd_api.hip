@@ -120,17 +120,21 @@ hipError_t gemm(const csd_head* hd, GemmArgs g, hipStream_t st) {
     return hd->cfg.gemm_dtype == CSD_BF16 ? launch_gemm_bf16(g, st) : launch_gemm_f32(g, st);
 }
 
-// optional hipEvent bracket around the dominant kernel (csd_profile_*)
+// optional timing of the dominant kernel (csd_profile_*): a hipEvent bracket on its launch stream,
+// and (bf16 kernels) the span from the first workgroup's start to the last one's end on the device
 struct Profile {
     std::vector<hipEvent_t> ev;     // 2 per launch
     std::vector<double> flops;
+    unsigned long long* d_pair = nullptr;    // [max][2] device: start preset to ~0, end to 0
     size_t used = 0;                // launches recorded
     bool on = false;
 } g_prof;
 
-hipError_t gemm_timed(const csd_head* hd, const GemmArgs& g, hipStream_t st) {
-    if (!g_prof.on || g_prof.used * 2 + 2 > g_prof.ev.size()) return gemm(hd, g, st);
+hipError_t gemm_timed(const csd_head* hd, const GemmArgs& g_in, hipStream_t st) {
+    if (!g_prof.on || g_prof.used * 2 + 2 > g_prof.ev.size()) return gemm(hd, g_in, st);
     const size_t i = g_prof.used;
+    GemmArgs g = g_in;
+    g.ts = g_prof.d_pair ? g_prof.d_pair + 2 * i : nullptr;
     hipError_t e = hipEventRecord(g_prof.ev[2 * i], st);
     if (e != hipSuccess) return e;
     if ((e = gemm(hd, g, st)) != hipSuccess) return e;
@@ -762,6 +766,7 @@ int csd_resample(const float* summary, const int32_t* n_accept, int64_t n_groups
 int csd_profile_enable(int32_t max_launches) {
     for (hipEvent_t ev : g_prof.ev) (void)hipEventDestroy(ev);
     g_prof.ev.clear(); g_prof.flops.clear(); g_prof.used = 0; g_prof.on = false;
+    if (g_prof.d_pair) { (void)hipFree(g_prof.d_pair); g_prof.d_pair = nullptr; }
     if (max_launches <= 0) return CSD_OK;
     if (max_launches > (1 << 20)) return fail(CSD_EINVAL, "csd_profile_enable: at most 2^20 launches");
     g_prof.ev.resize((size_t)max_launches * 2);
@@ -773,11 +778,16 @@ int csd_profile_enable(int32_t max_launches) {
             return fail(CSD_EHIP, "csd_profile_enable: hipEventCreate: %s", hipGetErrorString(e));
         }
     }
+    // [start, end] per launch: start preset to all ones (atomicMin), end to zero (atomicMax)
+    std::vector<unsigned long long> init((size_t)max_launches * 2);
+    for (size_t i = 0; i < init.size(); i += 2) { init[i] = ~0ull; init[i + 1] = 0ull; }
+    HIP_TRY(hipMalloc((void**)&g_prof.d_pair, init.size() * sizeof(unsigned long long)));
+    HIP_TRY(hipMemcpy(g_prof.d_pair, init.data(), init.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
     g_prof.on = true;
     return CSD_OK;
 }
 
-int csd_profile_read(double* ms_sum, int64_t* launches, double* flops_sum) {
+int csd_profile_read(double* ms_sum, int64_t* launches, double* flops_sum, double* ms_sum_on_device) {
     if (!ms_sum || !launches || !flops_sum) return fail(CSD_EINVAL, "csd_profile_read: NULL output");
     double ms = 0.0, fl = 0.0;
     for (size_t i = 0; i < g_prof.used; ++i) {
@@ -785,6 +795,21 @@ int csd_profile_read(double* ms_sum, int64_t* launches, double* flops_sum) {
         float t = 0.f;
         HIP_TRY(hipEventElapsedTime(&t, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]));
         ms += t; fl += g_prof.flops[i];
+    }
+    if (ms_sum_on_device) {
+        *ms_sum_on_device = 0.0;
+        if (g_prof.d_pair && g_prof.used) {
+            std::vector<unsigned long long> ts(g_prof.used * 2);
+            HIP_TRY(hipMemcpy(ts.data(), g_prof.d_pair, ts.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+            double ticks = 0.0;
+            bool all = true;
+            for (size_t i = 0; i < g_prof.used; ++i) {
+                if (ts[2 * i + 1] > ts[2 * i]) ticks += (double)(ts[2 * i + 1] - ts[2 * i]); else all = false;
+            }
+            *ms_sum_on_device = all ? ticks / 1e5 : 0.0;      // 100 MHz constant clock; 0 = not available (fp32 kernels)
+            for (size_t i = 0; i < ts.size(); i += 2) { ts[i] = ~0ull; ts[i + 1] = 0ull; }
+            HIP_TRY(hipMemcpy(g_prof.d_pair, ts.data(), ts.size() * sizeof(unsigned long long), hipMemcpyHostToDevice));
+        }
     }
     *ms_sum = ms; *launches = (int64_t)g_prof.used; *flops_sum = fl;
     g_prof.used = 0; g_prof.flops.clear();

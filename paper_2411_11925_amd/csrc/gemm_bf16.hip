@@ -43,6 +43,7 @@ struct Params {
     int M, N, K;
     int tiles_m, tiles_n;
     int panel;                  // > 0: an XCD walks its tiles in column panels of this many N-tiles
+    unsigned long long* ts;     // optional: [0] min start, [1] max end over the workgroups (profiling)
 };
 
 // s_waitcnt with only vmcnt set (expcnt and lgkmcnt left at "don't wait")
@@ -69,6 +70,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     constexpr int STAGE_B = (BM + BN) * ROW_B;
     static_assert(NW * 32 * TN * 4 <= NST * STAGE_B, "epilogue staging must fit in the LDS of the main loop");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    if (p.ts && threadIdx.x == 0) atomicMin(p.ts, (unsigned long long)__builtin_amdgcn_s_memrealtime());
 
     // ---- tile of this workgroup: ids sharing id%8 (one XCD) sweep n first, then m
     int tm, tn;
@@ -315,6 +317,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
         }
     };
     if (m0 + BM <= p.M) emit(std::false_type{}); else emit(std::true_type{});
+    if (p.ts && (threadIdx.x & 63) == 0) atomicMax(p.ts + 1, (unsigned long long)__builtin_amdgcn_s_memrealtime());
 }
 
 template <int BM, int BN, int WM, int WN, int BK, int NST, bool PIPE = false>
@@ -322,7 +325,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     Params p;
     p.A = (const bf16_t*)g.A; p.lda = g.lda; p.B = (const bf16_t*)g.B; p.bias = g.bias;
     p.C = g.C; p.ldc = g.ldc; p.gate = (const bf16_t*)g.gate; p.ldg = g.ldg;
-    p.M = g.M; p.N = g.N; p.K = g.K;
+    p.M = g.M; p.N = g.N; p.K = g.K; p.ts = g.ts;
     p.tiles_m = (g.M + BM - 1) / BM; p.tiles_n = g.N / BN;
     p.panel = 0;
     if (p.tiles_n > 16)

@@ -87,6 +87,8 @@ struct GemmArgs {
     int M, N, K;
     int epi;
     int c_is_f32;                  // output type override: 1 = fp32 even in bf16 mode
+    unsigned long long* ts;        // optional, device: ts[0] = min start, ts[1] = max end of the workgroups (100 MHz
+                                   // constant clock), for profiling; bf16 kernels only
 };
 
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t st);
