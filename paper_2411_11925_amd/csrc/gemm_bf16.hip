@@ -4,7 +4,8 @@
 // One workgroup owns a BM x BN tile of C and walks K in slabs of BK = 64.  Each slab
 // of A and B goes from global memory STRAIGHT INTO LDS (global_load_lds, 16 bytes per
 // lane, no staging registers), double-buffered: the loads of slab k+1 are in flight
-// while the MFMAs of slab k run, and one barrier per slab separates the two.
+// while the MFMAs of slab k run, and one barrier per slab separates the two.  (Large
+// launches use the software-pipelined form of this loop, see PIPE below.)
 // A direct load writes 64 lanes x 16 bytes contiguously, i.e. 8 LDS rows of 128 bytes,
 // so rows cannot be padded; bank conflicts of the fragment reads (32 rows, one 16-byte
 // chunk each) are avoided by an XOR swizzle instead: logical chunk c of row r lives at
@@ -354,7 +355,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     return hipGetLastError();
 }
 
-// tuning hook: environment variable CSD_GEMM_VARIANT = 0..9 forces a tile shape / main loop
+// tuning hook: environment variable CSD_GEMM_VARIANT forces a tile shape / main loop (see launch_gemm_bf16)
 int gemm_variant_override() {
     static int v = -2;
     if (v == -2) { const char* e = getenv("CSD_GEMM_VARIANT"); v = (e && *e) ? atoi(e) : -1; }
@@ -368,37 +369,30 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
     if (g.K % 64 != 0 || g.N % 64 != 0 || g.lda % 8 != 0 || g.ldc % 4 != 0) return hipErrorInvalidValue;
     if (((uintptr_t)g.A & 15u) || ((uintptr_t)g.B & 15u) || ((uintptr_t)g.C & 15u)) return hipErrorInvalidValue;
     if (g.epi == EPI_GATE_RES && (g.ldg % 4 != 0 || ((uintptr_t)g.gate & 7u))) return hipErrorInvalidValue;
+    // Tile shapes (CSD_GEMM_VARIANT forces one where it fits, a tuning hook):
+    //   9  256x256, 8 waves of 128x64, software-pipelined main loop - every large launch
+    //   1  the same tile with the plain two-stage loop (also serves K < 256)
+    //   8  256x192, 8 waves of 64x96: large launches whose N only 192 divides.  (Alone on the chip it
+    //      also wins where both divide, e.g. N = 2304: 949 against 878 TFLOP/s, but it moves 17 % more
+    //      bytes from L2 per flop and loses on the whole path, where several chains share the chip.)
+    //   3  64x64, 4 waves: below 2048 rows a launch is latency-bound and wants many small workgroups
+    //      (one head pass at 256 / 1024 rows: 263 / 290 us against 343 / 366 with 128x128 tiles; a
+    //      deeper ring of slabs buys nothing there)
     int variant = gemm_variant_override();
-    if (variant < 0) {
-        // large problems: 256-row tiles, 256 (or 192) columns wide
-        // (192 wins for one GEMM alone on the chip, e.g. 16384x768x768: 28 vs 34 us, but loses 5 % on
-        // the whole path, where several chains share the chip; it is used only where 256 does not divide N)
-        static int pref192 = -1;
-        if (pref192 < 0) { const char* e = getenv("CSD_GEMM_192"); pref192 = (e && *e == '1') ? 1 : 0; }
-        if (pref192 && g.M >= 2048 && g.N % 768 == 0 && g.N % 1024 != 0) variant = 8;
-        else if (g.M >= 2048 && g.N % 256 == 0) variant = 9;
+    if (variant != 1 && variant != 3 && variant != 8 && variant != 9) {
+        if (g.M >= 2048 && g.N % 256 == 0) variant = 9;
         else if (g.M >= 2048 && g.N % 192 == 0) variant = 8;
-        // below that the launch is latency-bound and wants many small workgroups: the 64x64 tile beats
-        // 128x128 at every M measured (one head pass at 256 / 1024 rows: 263 / 290 us against 343 / 366),
-        // and a deeper ring of slabs buys nothing there
         else variant = 3;
     }
-    if ((variant == 0 || variant == 1 || variant == 9) && g.N % 256 != 0) variant = (g.N % 192 == 0 && g.M >= 2048) ? 8 : 3;
+    if ((variant == 1 || variant == 9) && g.N % 256 != 0) variant = (g.N % 192 == 0) ? 8 : 3;
     if (variant == 8 && g.N % 192 != 0) variant = 3;
-    if ((variant == 2 || (variant >= 4 && variant < 8)) && g.N % 128 != 0) variant = 3;
-    if (variant == 7) variant = 9;
     switch (variant) {
-        case 0: return launch_cfg<256, 256, 2, 2, 64, 2>(g, st);    // 4 waves, 128x128 per wave, 128 KiB LDS
-        case 1: return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);    // 8 waves, 128x64 per wave, 128 KiB LDS
-        case 2: return launch_cfg<128, 128, 2, 2, 64, 2>(g, st);    // 4 waves, 64x64 per wave, 64 KiB LDS
-        case 4: return launch_cfg<256, 128, 2, 2, 32, 3>(g, st);    // 4 waves, 128x64 per wave, 72 KiB LDS: 2 per CU
-        case 5: return launch_cfg<256, 128, 2, 2, 32, 2>(g, st);    // same, 48 KiB LDS
-        case 6: return launch_cfg<256, 128, 2, 2, 64, 2>(g, st);    // same tile, BK 64, 96 KiB LDS
-        case 9: if (g.K >= 256) return launch_cfg<256, 256, 2, 4, 64, 2, true>(g, st);   // 8 waves, software-pipelined main loop
+        case 1: return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);
+        case 9: if (g.K >= 256) return launch_cfg<256, 256, 2, 4, 64, 2, true>(g, st);
                 return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);
         case 8: if (g.K >= 256) return launch_cfg<256, 192, 4, 2, 64, 2, true>(g, st);
-                return launch_cfg<256, 192, 4, 2, 64, 2>(g, st);    // 8 waves, 64x96 per wave: N = 3 * 2^k widths
-        default: return launch_cfg<64, 64, 2, 2, 64, 2>(g, st);     // 4 waves, 32x32 per wave
+                return launch_cfg<256, 192, 4, 2, 64, 2>(g, st);
+        default: return launch_cfg<64, 64, 2, 2, 64, 2>(g, st);
     }
 }
 
