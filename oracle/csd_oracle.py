@@ -251,6 +251,7 @@ class HeadCfg:
     eps_skip_gain: float = 0.0      # eps_hat = gain * sqrt(1-abar_t) * x_t + o[:D]
     sampler: str = "ddpm"           # "ddpm" (Eq. 3, learned-range variance) | "ddim" (App., other samplers)
     ddim_eta: float = 1.0           # DDIM: sigma_t^2 = eta^2 * beta~_t
+    cfg_scale: float | None = None  # classifier-free guidance: z then holds (cond, uncond) per row
 
 
 def head_param_shapes(cfg: HeadCfg):
@@ -314,12 +315,25 @@ class Head:
             self.time_emb[t] = self.p["t2.w"] @ a + self.p["t2.b"]
 
     def cond_embed(self, z):
-        """e = W_c z + b_c, once per row (it does not depend on t)."""
+        """e = W_c z + b_c, once per row (it does not depend on t).  With guidance z is
+        [R, 2, C] (the conditional vector, then the unconditional one) and e [R, 2, W]."""
+        z = np.asarray(z, dtype=np.float64)
+        if self.cfg.cfg_scale is not None:
+            z = z.reshape(z.shape[0], 2, self.cfg.cond_dim)
         return z @ self.p["cond.w"].T + self.p["cond.b"]
 
     def forward(self, x, t: int, e):
-        """(eps_hat, v) = Head(x_t, t, z) for a batch of rows.
-        x [R,D], e = cond_embed(z) [R,W]."""
+        """(eps_hat, v) = Head(x_t, t, z) for a batch of rows.  x [R,D], e = cond_embed(z).
+        With classifier-free guidance (scale s): the head is evaluated with the conditional
+        and with the unconditional vector on the same x_t,
+        eps_hat = eps_u + s (eps_c - eps_u), and v is the conditional one."""
+        if self.cfg.cfg_scale is not None:
+            eh_c, v_c = self._forward(x, t, e[:, 0])
+            eh_u, _ = self._forward(x, t, e[:, 1])
+            return eh_u + self.cfg.cfg_scale * (eh_c - eh_u), v_c
+        return self._forward(x, t, e)
+
+    def _forward(self, x, t: int, e):
         p, cfg = self.p, self.cfg
         W, D = cfg.width, cfg.token_dim
         s = silu(self.time_emb[t] + e)

@@ -618,3 +618,34 @@ def test_ddim_heads_run_the_whole_path_with_sigma_factor_one():
     same, _ = O.denoise_lockstep(tgt, tgt, zq, zq, seed=9)
     n_acc, ell2, mask, _ = O.verify(same, 6, 4, 9)
     assert np.all(ell2 == 0.0) and np.all(n_acc == 4)
+
+
+# ------------------------------------------------------ classifier-free guidance ----
+def test_guidance_special_cases_and_linearity():
+    """eps_hat = eps_u + s (eps_c - eps_u): s = 1 is the conditional head, s = 0 the
+    unconditional eps with the conditional v, equal vectors make s irrelevant, and eps_hat is
+    affine in s; the guided head is still one Gaussian step, so identical guided heads accept
+    everything."""
+    shape = S.HeadShape(8, 6, 16, 2)
+    blob = S.head_weights(shape, 7, 0.3, 0.1)
+    plain = O.Head(O.HeadCfg(8, 6, 16, 2, 6, eps_skip_gain=1.0), blob)
+    rng = np.random.default_rng(1)
+    x = rng.normal(size=(9, 8)); zc = rng.normal(size=(9, 6)); zu = rng.normal(size=(9, 6))
+    z2 = np.stack([zc, zu], axis=1)
+    ec, vc = plain.forward(x, 3, plain.cond_embed(zc))
+    eu, vu = plain.forward(x, 3, plain.cond_embed(zu))
+    out = {}
+    for s in (0.0, 1.0, 2.0, 3.5):
+        g = O.Head(O.HeadCfg(8, 6, 16, 2, 6, eps_skip_gain=1.0, cfg_scale=s), blob)
+        out[s] = g.forward(x, 3, g.cond_embed(z2.reshape(9, 12)))
+        assert np.array_equal(out[s][1], vc)
+    assert np.allclose(out[1.0][0], ec, rtol=1e-13) and np.allclose(out[0.0][0], eu, rtol=1e-13)
+    assert np.allclose(out[2.0][0] - out[1.0][0], out[1.0][0] - out[0.0][0], atol=1e-12)
+    assert np.allclose(out[3.5][0], eu + 3.5 * (ec - eu), atol=1e-12) and not np.allclose(ec, eu)
+    g = O.Head(O.HeadCfg(8, 6, 16, 2, 6, eps_skip_gain=1.0, cfg_scale=2.5), blob)
+    same = np.stack([zc, zc], axis=1)
+    assert np.allclose(g.forward(x, 3, g.cond_embed(same))[0], ec, rtol=1e-12)
+    zz = rng.normal(size=(24, 2, 6))
+    summ, _ = O.denoise_lockstep(g, g, zz, zz, seed=4)
+    n_acc, ell, mask, _ = O.verify(summ, 6, 4, 4)
+    assert np.all(ell == 0.0) and np.all(n_acc == 4)
