@@ -54,6 +54,8 @@ def main():
     ap.add_argument("--rows", type=int, default=0, help="rows per step (default: the whole workload)")
     ap.add_argument("--oracle-rows", type=int, default=128, help="rows of the CPU-oracle sample (0: skip)")
     ap.add_argument("--ddim-eta", type=float, default=None, help="use the DDIM sampler with this eta (default: DDPM)")
+    ap.add_argument("--cfg-scale", type=float, default=None,
+                    help="classifier-free guidance with this scale in both heads (two conditioning vectors per row)")
     ap.add_argument("--no-latency-shape", action="store_true", help="skip the split-phase latency-shape figure")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 256 MiB device to device once (a kernel of known "
@@ -82,6 +84,14 @@ def main():
                                eps_skip_gain=wl.eps_skip_gain, ddim_eta=a.ddim_eta)
     h_q, h_p = B.csd_init_head(mk(ds), db), B.csd_init_head(mk(wl.target), tb)
     zq_h, zp_h = wl.conds(((R + 63) // 64) * 64)
+    reps = 1
+    if a.cfg_scale is not None:
+        # unconditional vectors: the workload's vectors of another block of rows
+        uq_h, up_h = wl.conds(((R + 63) // 64) * 64, 64 * (1 << 20))
+        zq_h, zp_h = np.stack([zq_h, uq_h], 1), np.stack([zp_h, up_h], 1)
+        B.csd_set_guidance(h_q, True, a.cfg_scale); B.csd_set_guidance(h_p, True, a.cfg_scale)
+        reps = 2
+        a.no_latency_shape = True
     z_q, z_p = torch.from_numpy(zq_h[:R]).to(dev), torch.from_numpy(zp_h[:R]).to(dev)
     ws = torch.empty(B.csd_workspace_bytes(h_q, h_p, R), dtype=torch.uint8, device=dev)
     summary = torch.empty((R, 5 * D + 1), dtype=torch.float32, device=dev)
@@ -138,8 +148,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    flops_row = wl.n_steps * (head_flops_per_row_step(wl.target) + head_flops_per_row_step(ds)) \
-        + 2 * wl.target.cond_dim * (wl.target.width + ds.width)
+    flops_row = reps * (wl.n_steps * (head_flops_per_row_step(wl.target) + head_flops_per_row_step(ds))
+                        + 2 * wl.target.cond_dim * (wl.target.width + ds.width))
     tokens_per_s = R * a.steps / (ms / 1e3)
     achieved = (k_flops / k_n) / (k_ms / k_n / 1e3) / 1e12 if k_n else 0.0
     peak = PEAK[dtype]
@@ -160,7 +170,8 @@ def main():
             wl.name, wl.target.n_blocks, wl.target.width, ds.n_blocks, ds.width, wl.target.cond_dim,
             wl.n_steps, R, G, gamma), "rows_per_step": R, "gamma": gamma, "out_scale": wl.out_scale,
             "eps_skip_gain": wl.eps_skip_gain,
-            "sampler": "ddpm" if a.ddim_eta is None else "ddim(eta=%g)" % a.ddim_eta},
+            "sampler": "ddpm" if a.ddim_eta is None else "ddim(eta=%g)" % a.ddim_eta,
+            "cfg_scale": a.cfg_scale},
         "wall_s": wall,
         "whole_path": {"algorithmic_TFLOP_per_s": flops_row * R * a.steps / (ms / 1e3) / 1e12,
                        "frac_of_peak": flops_row * R * a.steps / (ms / 1e3) / 1e12 / peak,
@@ -227,6 +238,8 @@ def main():
             cores = os.cpu_count()
         n = min(a.oracle_rows // gamma * gamma, R)
         samp = dict(sampler="ddim", ddim_eta=a.ddim_eta) if a.ddim_eta is not None else {}
+        if a.cfg_scale is not None:
+            samp["cfg_scale"] = a.cfg_scale
         ocfg = lambda sh: O.HeadCfg(sh.token_dim, sh.cond_dim, sh.width, sh.n_blocks, wl.n_steps,
                                     eps_skip_gain=wl.eps_skip_gain, **samp)
         t0 = time.perf_counter()

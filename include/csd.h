@@ -128,6 +128,18 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
 void csd_free_head(csd_head_t* head);
 
 /*
+ * Classifier-free guidance for this head (the paper's runs use it, Sec. 4 and the appendix
+ * on guidance scale; how it enters the head is not spelled out there).  Reading taken: while
+ * enabled, every conditioning array passed for this head holds TWO vectors per row, [R, 2, C]
+ * = (conditional, unconditional); each step evaluates the head with both on the same x_t and
+ *   eps_hat = eps_u + scale (eps_c - eps_u),   v = v_c.
+ * The guided head is still one Gaussian step, so everything downstream is unchanged.
+ * scale = 1 is the conditional head.  Workspace needs grow (csd_workspace_bytes accounts for
+ * it).  A setting, not per-call state: do not change it while calls on this head are in flight.
+ */
+int csd_set_guidance(csd_head_t* head, int32_t enabled, float scale);
+
+/*
  * Bytes of device workspace csd_denoise_lockstep / csd_head_eval need for
  * n_rows rows with these heads (either head may be NULL).  0 on invalid input.
  */

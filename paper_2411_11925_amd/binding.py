@@ -30,7 +30,7 @@ CSD_STREAM_BONUS = 4
 CSD_SAMPLER_DDPM, CSD_SAMPLER_DDIM = 0, 1
 CSD_FLAG_CAP, CSD_FLAG_NONFINITE = 1, 2
 
-EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_workspace_bytes",
+EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_set_guidance", "csd_workspace_bytes",
            "csd_denoise_lockstep", "csd_denoise_draft", "csd_denoise_target", "csd_sample",
            "csd_verify", "csd_resample", "csd_append_bonus", "csd_head_eval",
            "csd_rng_normals", "csd_rng_uniforms", "csd_gemm_bf16", "csd_profile_enable", "csd_profile_read", "csd_last_error"]
@@ -52,6 +52,8 @@ _lib.csd_init_head.restype = c_int
 _lib.csd_init_head.argtypes = [POINTER(csd_head_cfg_t), c_void_p, c_size_t, c_int, POINTER(c_void_p)]
 _lib.csd_free_head.restype = None
 _lib.csd_free_head.argtypes = [c_void_p]
+_lib.csd_set_guidance.restype = c_int
+_lib.csd_set_guidance.argtypes = [c_void_p, c_int32, c_float]
 _lib.csd_workspace_bytes.restype = c_size_t
 _lib.csd_workspace_bytes.argtypes = [c_void_p, c_void_p, c_int64]
 _lib.csd_denoise_lockstep.restype = c_int
@@ -142,6 +144,7 @@ class Head:
 
     def __init__(self, handle: int, cfg: csd_head_cfg_t, device: int):
         self.handle, self.cfg, self.device = handle, cfg, device
+        self.reps = 1          # conditioning vectors per row: 2 with classifier-free guidance
 
     def free(self):
         if self.handle:
@@ -166,6 +169,11 @@ def csd_free_head(head: Head):
     head.free()
 
 
+def csd_set_guidance(head: Head, enabled: bool, scale: float = 1.0):
+    _check(_lib.csd_set_guidance(head.handle, 1 if enabled else 0, scale))
+    head.reps = 2 if enabled else 1
+
+
 def csd_workspace_bytes(draft: Head | None, target: Head | None, n_rows: int) -> int:
     return int(_lib.csd_workspace_bytes(draft.handle if draft else None, target.handle if target else None, n_rows))
 
@@ -182,7 +190,7 @@ def csd_denoise_lockstep(draft: Head, target: Head, z_q: torch.Tensor, z_p: torc
     R, D = n_groups * gamma, draft.cfg.token_dim
     assert z_q.is_cuda and z_p.is_cuda and z_q.dtype == torch.float32 and z_p.dtype == torch.float32
     assert z_q.is_contiguous() and z_p.is_contiguous()
-    assert tuple(z_q.shape) == (R, draft.cfg.cond_dim) and tuple(z_p.shape) == (R, target.cfg.cond_dim)
+    assert z_q.numel() == R * draft.reps * draft.cfg.cond_dim and z_p.numel() == R * target.reps * target.cfg.cond_dim
     if summary is None:
         summary = torch.empty((R, 5 * D + 1), dtype=torch.float32, device=z_q.device)
     assert summary.is_contiguous() and tuple(summary.shape) == (R, 5 * D + 1) and summary.dtype == torch.float32
@@ -199,7 +207,7 @@ def csd_denoise_draft(draft: Head, z_q: torch.Tensor, n_groups: int, gamma: int,
                       workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
     D = draft.cfg.token_dim
     assert z_q.is_cuda and z_q.dtype == torch.float32 and z_q.is_contiguous()
-    assert tuple(z_q.shape) == (n_groups, draft.cfg.cond_dim)
+    assert z_q.numel() == n_groups * draft.reps * draft.cfg.cond_dim
     assert summary.is_cuda and summary.is_contiguous() and summary.dtype == torch.float32
     assert tuple(summary.shape) == (n_groups * gamma, 5 * D + 1)
     if workspace is None:
@@ -214,7 +222,7 @@ def csd_denoise_target(target: Head, draft: Head, z_p: torch.Tensor, n_groups: i
                        workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
     R, D = n_groups * gamma, target.cfg.token_dim
     assert z_p.is_cuda and z_p.dtype == torch.float32 and z_p.is_contiguous()
-    assert tuple(z_p.shape) == (R, target.cfg.cond_dim)
+    assert z_p.numel() == R * target.reps * target.cfg.cond_dim
     assert summary.is_cuda and summary.is_contiguous() and summary.dtype == torch.float32
     assert tuple(summary.shape) == (R, 5 * D + 1)
     if workspace is None:
@@ -228,7 +236,8 @@ def csd_sample(head: Head, z: torch.Tensor, seed: int, row_offset: int = 0, rng_
                temperature: float = 1.0, tokens: torch.Tensor | None = None,
                workspace: torch.Tensor | None = None, stream=None) -> torch.Tensor:
     n, D = z.shape[0], head.cfg.token_dim
-    assert z.is_cuda and z.dtype == torch.float32 and z.is_contiguous() and z.shape[1] == head.cfg.cond_dim
+    assert z.is_cuda and z.dtype == torch.float32 and z.is_contiguous()
+    assert z.numel() == n * head.reps * head.cfg.cond_dim
     if tokens is None:
         tokens = torch.empty((n, D), dtype=torch.float32, device=z.device)
     assert tokens.is_cuda and tokens.is_contiguous() and tokens.dtype == torch.float32 and tuple(tokens.shape) == (n, D)
@@ -287,7 +296,7 @@ def csd_head_eval(head: Head, x: torch.Tensor, z: torch.Tensor, t: int, workspac
     R, D = x.shape[0], head.cfg.token_dim
     assert x.is_cuda and z.is_cuda and x.dtype == torch.float32 and z.dtype == torch.float32
     assert x.is_contiguous() and z.is_contiguous()
-    assert tuple(x.shape) == (R, D) and tuple(z.shape) == (R, head.cfg.cond_dim)
+    assert tuple(x.shape) == (R, D) and z.numel() == R * head.reps * head.cfg.cond_dim
     out = torch.empty((R, 2 * D), dtype=torch.float32, device=x.device)
     if workspace is None:
         workspace, _ = _workspace(head, None, R, x.device)

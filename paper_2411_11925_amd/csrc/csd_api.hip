@@ -75,15 +75,16 @@ size_t batched_bytes_per_row(const csd_head* hd) {
 // steps per batch for a call of R rows (row chunks of the call use the same value)
 int steps_per_batch(const csd_head* hd, int64_t R) {
     if (R <= 0) return 1;
-    const size_t per_step = (size_t)R * batched_bytes_per_row(hd);
+    const size_t per_step = (size_t)R * hd->reps * batched_bytes_per_row(hd);
     size_t tb = BATCH_BUDGET / per_step;
     if (tb < 1) tb = 1;
     if (tb > (size_t)hd->T) tb = (size_t)hd->T;
     return (int)tb;
 }
 
+// (R = trajectory rows; the head's activations have R * reps rows: 2 per row with guidance)
 size_t head_ws_bytes(const csd_head* hd, int64_t R, int tb) {
-    const size_t r = (size_t)R, W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
+    const size_t r = (size_t)R * hd->reps, W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
     size_t n = 0;
     n += align_up(r * W * 4, 256);          // e
     n += align_up(tb * r * W * act, 256);   // s
@@ -93,13 +94,13 @@ size_t head_ws_bytes(const csd_head* hd, int64_t R, int tb) {
     n += align_up(r * W * 4, 256);          // u (fp32, bf16, or the [hi|lo] bf16 pair of the last layer)
     n += 2 * align_up(r * W * act, 256);    // a, y
     n += align_up(r * 64 * 4, 256);         // o (output projection, padded to 64 columns)
-    n += align_up(r * hd->D * 4, 256);      // x
-    n += align_up(r * 4, 256);              // acc
+    n += align_up((size_t)R * hd->D * 4, 256);      // x
+    n += align_up((size_t)R * 4, 256);              // acc
     return n;
 }
 
 char* carve(const csd_head* hd, int64_t R, int tb, char* p, HeadWs* ws) {
-    const size_t r = (size_t)R, W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
+    const size_t r = (size_t)R * hd->reps, W = hd->W, act = hd->cfg.gemm_dtype == CSD_BF16 ? 2 : 4;
     auto take = [&](size_t bytes) { char* q = p; p += align_up(bytes, 256); return q; };
     ws->tb = tb;
     ws->e = (float*)take(r * W * 4);
@@ -111,8 +112,8 @@ char* carve(const csd_head* hd, int64_t R, int tb, char* p, HeadWs* ws) {
     ws->a = take(r * W * act);
     ws->y = take(r * W * act);
     ws->o = (float*)take(r * 64 * 4);
-    ws->x = (float*)take(r * hd->D * 4);
-    ws->acc = (float*)take(r * 4);
+    ws->x = (float*)take((size_t)R * hd->D * 4);
+    ws->acc = (float*)take((size_t)R * 4);
     return p;
 }
 
@@ -208,7 +209,7 @@ hipError_t phase_elem(const csd_head* hd, const HeadWs& ws, int p, int k, int64_
     BlockPreArgs bp{};
     bp.act = b16 ? ACT_BF16 : ACT_F32; bp.h = ws.h; bp.y = ws.y; bp.u = ws.u; bp.ln_eps = hd->ln_eps;
     bp.R = R; bp.W = W; bp.D = hd->D;
-    bp.x = ws.x; bp.w_in = hd->in.w; bp.b_in = hd->in.b; bp.w_in_t = hd->d_in_t;
+    bp.x = ws.x; bp.x_div = hd->reps; bp.w_in = hd->in.w; bp.b_in = hd->in.b; bp.w_in_t = hd->d_in_t;
     bp.mode = (p == 0) ? 0 : (p == L ? 2 : 1);
     const int ld_all = 3 * W * L;          // block l's (shift, scale, gate) sit at columns [l*3W, (l+1)*3W) of a mod row
     const char* mod_k = (const char*)ws.mod + (size_t)k * R * ld_all * asz;        // step k of the batch
@@ -233,6 +234,7 @@ TransArgs trans_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
     f.o = ws.o; f.ldo = 64; f.R = R; f.D = hd->D; f.x = ws.x; f.acc = ws.acc;
     f.coef = hd->coef[t]; f.t = t;
     f.row_stride = 1; f.row_shift = 0; f.rng_stream = CSD_STREAM_TRAJ;
+    f.reps = hd->reps; f.cfg_scale = hd->cfg_scale;
     return f;
 }
 
@@ -317,14 +319,15 @@ int run_chains(Chain* chains, int n_chains, uint64_t seed, float tau, hipStream_
         Chain& ch = chains[i];
         HIP_TRY(launch_init_x(ch.ws.x, ch.ws.acc, ch.n, ch.hd->D, T, seed, ch.row_offset, ch.row_stride, ch.row_shift,
                               ch.rng_stream, ch.s));
-        HIP_TRY(cond_embed(ch.hd, ch.z, ch.ws, ch.n, ch.s));
+        HIP_TRY(cond_embed(ch.hd, ch.z, ch.ws, ch.n * ch.hd->reps, ch.s));
     }
     for (int t = T; t >= 1; --t) {
         for (int i = 0; i < n_chains; ++i) {
             Chain& ch = chains[i];
             const int k = (T - t) % ch.ws.tb;
-            if (k == 0) HIP_TRY(batch_stage(ch.hd, ch.ws, t, t < ch.ws.tb ? t : ch.ws.tb, ch.n, ch.s));
-            HIP_TRY(head_body(ch.hd, ch.ws, k, ch.n, ch.s));
+            const int64_t nh = ch.n * ch.hd->reps;      // rows of the head's activations
+            if (k == 0) HIP_TRY(batch_stage(ch.hd, ch.ws, t, t < ch.ws.tb ? t : ch.ws.tb, nh, ch.s));
+            HIP_TRY(head_body(ch.hd, ch.ws, k, nh, ch.s));
             TransArgs f = trans_args(ch.hd, ch.ws, t, ch.n);
             f.seed = seed; f.row_offset = ch.row_offset; f.tau = tau;
             f.row_stride = ch.row_stride; f.row_shift = ch.row_shift; f.rng_stream = ch.rng_stream;
@@ -360,7 +363,7 @@ int run_single_head(const csd_head* hd, const float* z, int64_t n, uint64_t seed
     for (int c = 0; c < n_chunks; ++c) {
         const int64_t r0 = c * chunk_rows, m = (n - r0 < chunk_rows) ? n - r0 : chunk_rows;
         Chain& ch = chains[c];
-        ch.hd = hd; ch.n = m; ch.z = z + r0 * hd->C;
+        ch.hd = hd; ch.n = m; ch.z = z + r0 * hd->reps * hd->C;
         ch.row_offset = row_offset + (uint64_t)(r0 * row_stride); ch.row_stride = row_stride; ch.row_shift = row_shift;
         ch.rng_stream = rng_stream; ch.is_target = is_target;
         ch.summary = summary ? summary + r0 * row_stride * (5 * hd->D + 1) : nullptr;
@@ -395,6 +398,15 @@ void csd_free_head(csd_head_t* h) {
     if (h->d_mod_all) (void)hipFree(h->d_mod_all);
     if (h->d_mod_all_bias) (void)hipFree(h->d_mod_all_bias);
     delete h;
+}
+
+int csd_set_guidance(csd_head_t* head, int32_t enabled, float scale) {
+    if (!head) return fail(CSD_EINVAL, "csd_set_guidance: NULL head");
+    if (enabled && !(scale == scale && scale >= -64.f && scale <= 64.f))
+        return fail(CSD_EINVAL, "csd_set_guidance: scale must be a number in [-64, 64]");
+    head->reps = enabled ? 2 : 1;
+    head->cfg_scale = enabled ? scale : 0.f;
+    return CSD_OK;
 }
 
 int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n_floats, int device,
@@ -616,7 +628,7 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, cons
         const int64_t r0 = c * chunk_rows, n = (R - r0 < chunk_rows) ? R - r0 : chunk_rows;
         for (int which = 0; which < 2; ++which) {
             Chain& ch = chains[n_chains++];
-            ch.hd = which ? target : draft; ch.n = n; ch.z = (which ? z_p : z_q) + r0 * ch.hd->C;
+            ch.hd = which ? target : draft; ch.n = n; ch.z = (which ? z_p : z_q) + r0 * ch.hd->reps * ch.hd->C;
             ch.row_offset = row_offset + (uint64_t)r0; ch.row_stride = 1; ch.row_shift = 0; ch.rng_stream = CSD_STREAM_TRAJ;
             ch.summary = summary + r0 * (5 * D + 1); ch.is_target = which; ch.tokens = nullptr;
             wp_ = carve(ch.hd, n, steps_per_batch(ch.hd, R), wp_, &ch.ws);
@@ -725,9 +737,9 @@ int csd_head_eval(const csd_head_t* head, const float* x, const float* z, int32_
     HeadWs ws;
     carve(head, n_rows, steps_per_batch(head, n_rows), (char*)workspace, &ws);
     HIP_TRY(hipMemcpyAsync(ws.x, x, (size_t)n_rows * head->D * sizeof(float), hipMemcpyDeviceToDevice, st));
-    HIP_TRY(cond_embed(head, z, ws, n_rows, st));
-    HIP_TRY(batch_stage(head, ws, t, 1, n_rows, st));
-    HIP_TRY(head_body(head, ws, 0, n_rows, st));
+    HIP_TRY(cond_embed(head, z, ws, n_rows * head->reps, st));
+    HIP_TRY(batch_stage(head, ws, t, 1, n_rows * head->reps, st));
+    HIP_TRY(head_body(head, ws, 0, n_rows * head->reps, st));
     TransArgs f = trans_args(head, ws, t, n_rows);
     f.raw_out = out; f.skip_coef = head->skip_sqrt[t];
     HIP_TRY(launch_transition(f, st));

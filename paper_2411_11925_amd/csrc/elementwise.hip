@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void k_block_pre(BlockPreArgs a) {
     float xr[D];
     if (MODE == PRE_FIRST) {
 #pragma unroll
-        for (int d = 0; d < D; ++d) xr[d] = a.x[r * D + d];
+        for (int d = 0; d < D; ++d) xr[d] = a.x[(r / a.x_div) * D + d];
     }
     auto h_at = [&](int j, float out[4], int n) {        // n consecutive features from j
         if (MODE == PRE_FIRST) {
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void k_block_first(BlockPreArgs a) {
         const int64_t r = (r0 + rr < a.R) ? r0 + rr : a.R - 1;
 #pragma unroll
         for (int d = 0; d < D; ++d)      // the same value in every lane: keep it in a scalar register
-            xr[rr][d] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(a.x[r * D + d])));
+            xr[rr][d] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(a.x[(r / a.x_div) * D + d])));
     }
     float s[RPW], mean[RPW], q[RPW], rstd[RPW];
 #pragma unroll
@@ -306,7 +306,13 @@ __global__ void k_transition(TransArgs a) {
     const int64_t r = i / D;
     const int d = (int)(i % D);
     if (r >= a.R) return;                      // whole D-lane segments drop out together
-    const float o_eps = a.o[r * a.ldo + d], o_v = a.o[r * a.ldo + D + d];
+    const int64_t ro = r * a.reps;
+    float o_eps = a.o[ro * a.ldo + d];
+    const float o_v = a.o[ro * a.ldo + D + d];
+    if (a.reps == 2) {                         // classifier-free guidance: eps_u + s (eps_c - eps_u)
+        const float o_u = a.o[(ro + 1) * a.ldo + d];
+        o_eps = fmaf(a.cfg_scale, o_eps - o_u, o_u);
+    }
     const float x = a.x[r * D + d];
     if (a.raw_out) {
         a.raw_out[r * 2 * D + d] = fmaf(a.skip_coef, x, o_eps);

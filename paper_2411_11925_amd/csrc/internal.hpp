@@ -52,6 +52,8 @@ struct csd_head {
     int device;
     int D, C, W, L, T;
     float ln_eps;
+    int reps = 1;                        // head rows per trajectory row: 2 with classifier-free guidance
+    float cfg_scale = 0.f;               // guidance scale (reps == 2)
     csd::Linear t1, t2, cond, in, fmod, out;
     csd::Linear out_pad;                 // output layer padded to 64 rows; bf16 copy is [w | w] (2W per row)
     float* d_out_pad = nullptr;          // storage of out_pad (fp32 w, b)
@@ -109,6 +111,7 @@ struct BlockPreArgs {
     const float* x; const float* w_in; const float* b_in;   // mode 0: x [R,D], W_in [W,D], b_in [W]
     const float* w_in_t;       // mode 0, optional: W_in transposed to [D,W] (enables the 4-rows-per-wave path)
     float ln_eps; int64_t R; int W; int D;
+    int x_div;                 // mode 0: head row i reads x row i / x_div (2 with guidance: cond and uncond rows share x)
 };
 hipError_t launch_block_pre(const BlockPreArgs& a, hipStream_t st);
 
@@ -126,6 +129,8 @@ struct TransArgs {
     float* tokens;                   // optional [R,D]: t == 1 writes x_0 there instead (plain sampling)
     float* raw_out;            // optional [R,2D]: (eps_hat, v) for csd_head_eval; skips the transition
     float skip_coef;           // eps_skip_gain * sqrt(1 - abar_t), for raw_out only
+    int reps; float cfg_scale; // reps == 2: row r's outputs are o[2r] (conditional) and o[2r+1] (unconditional);
+                               // eps part = o_u + cfg_scale (o_c - o_u), v part = the conditional one
 };
 hipError_t launch_transition(const TransArgs& a, hipStream_t st);
 

@@ -67,6 +67,7 @@ def test_argument_errors_without_device_work(B):
     assert lib.csd_denoise_draft(None, None, 1, 1, 0, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
     assert lib.csd_denoise_target(None, None, None, 1, 1, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
     assert lib.csd_sample(None, None, 1, 0, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
+    assert lib.csd_set_guidance(None, 1, 1.0) == B.CSD_EINVAL
     assert lib.csd_append_bonus(None, None, None, None, 4, 0, 16, None) == B.CSD_EINVAL
     assert lib.csd_append_bonus(None, None, None, None, 4, 4, 5, None) == B.CSD_EINVAL
     assert lib.csd_append_bonus(None, None, None, None, 4, 4, 16, None) == B.CSD_EINVAL      # NULL buffers
