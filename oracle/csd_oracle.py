@@ -47,6 +47,12 @@ STREAM_ACCEPT_U = 1  # slot 0: the uniform r_i of the accept test
 STREAM_RESAMPLE_N = 2  # slot k: proposal noise of resampling trial k
 STREAM_RESAMPLE_U = 3  # slot k: uniform of resampling trial k
 STREAM_BONUS = 4     # trajectory noise of the target-only sample x ~ p_{gamma+1}, keyed by the global GROUP index
+STREAM_TRAJ_P = 5    # the target's own trajectory noise when the two paths are NOT aligned (ablation), slots as stream 0
+
+# how the path ratio before the final step is formed (Table 1 of the paper)
+RATIO_ALIGNED = 0      # p(Y_p)/q(Y_q), eps^p_t = eps^q_t: the method
+RATIO_UNALIGNED = 1    # p(Y_p)/q(Y_q), independent noise in the two paths
+RATIO_SINGLE_PATH = 2  # p(Y)/q(Y), both densities on the draft's path (Eq. 2)
 
 
 # --------------------------------------------------------------------------
@@ -404,8 +410,7 @@ def summary_width(D: int) -> int:
 
 def denoise_lockstep(draft: Head, target: Head, z_q, z_p, seed: int,
                      row_offset: int = 0, tau: float = 1.0,
-                     noise: np.ndarray | None = None, aligned: bool = True,
-                     return_trace: bool = False):
+                     noise: np.ndarray | None = None, return_trace: bool = False):
     """Run both heads from x_T = eps_T down to t = 1 with shared eps_t.
 
     Returns summary [R, 5D+1] = [mu^p_1 | logvar^p_1 | mu^q_1 | logvar^q_1 |
@@ -413,8 +418,7 @@ def denoise_lockstep(draft: Head, target: Head, z_q, z_p, seed: int,
       log_sigma_full : sum_{t=2..T} [log p(x^p_{t-1}|x^p_t) - log q(x^q_{t-1}|x^q_t)]
                        from the Gaussian pdfs themselves (Eq. 3, Eq. 6 left side)
       dist2          : ||x^q_0' - x^p_0'||^2 of the two models' own final samples.
-    `noise` ([T+1, R, D], slot-indexed) replaces the Philox stream if given;
-    `aligned=False` gives the target its own noise (ablation only)."""
+    `noise` ([T+1, R, D], slot-indexed) replaces the Philox stream if given."""
     D, T = draft.cfg.token_dim, draft.cfg.n_steps
     assert target.cfg.token_dim == D and target.cfg.n_steps == T
     z_q = np.asarray(z_q, dtype=np.float64)
@@ -440,9 +444,8 @@ def denoise_lockstep(draft: Head, target: Head, z_q, z_p, seed: int,
         mu_q, lv_q = head_transition(draft, x_q, t, eh_q, v_q)
         mu_p, lv_p = head_transition(target, x_p, t, eh_p, v_p)
         eps_t = eps(t - 1)
-        eps_t_p = eps_t if aligned else normals(seed ^ 0x5DEECE66D, rows, t - 1, STREAM_TRAJ, D)
         xn_q = mu_q + tau * np.exp(0.5 * lv_q) * eps_t
-        xn_p = mu_p + tau * np.exp(0.5 * lv_p) * eps_t_p
+        xn_p = mu_p + tau * np.exp(0.5 * lv_p) * eps_t
         if return_trace:
             trace.append(dict(t=t, x_q=x_q, x_p=x_p, mu_q=mu_q, mu_p=mu_p,
                               lv_q=lv_q, lv_p=lv_p, eh_q=eh_q, eh_p=eh_p))
@@ -461,6 +464,61 @@ def denoise_lockstep(draft: Head, target: Head, z_q, z_p, seed: int,
             if return_trace:
                 extras["trace"] = trace
             return summary, extras
+    raise AssertionError("T must be >= 1")
+
+
+# --------------------------------------------------------------------------
+# The three path ratios the paper compares (Table 1; the appendix on the
+# approximation of the ratio; the alignment ablation table)
+# --------------------------------------------------------------------------
+def denoise_ablation(draft: Head, target: Head, z_q, z_p, seed: int, row_offset: int = 0,
+                     tau: float = 1.0, mode: int = RATIO_ALIGNED):
+    """Both heads from x_T to t = 1 with the path ratio formed in one of three ways.
+
+    RATIO_ALIGNED      two paths Y_p, Y_q driven by the same noise (Sec. 3.2): the method.
+    RATIO_UNALIGNED    two paths with independent noise: the target draws x_T^p and every
+                       eps^p_t from STREAM_TRAJ_P, the draft from STREAM_TRAJ as always.
+    RATIO_SINGLE_PATH  one path, the draft's: the target head is evaluated at the draft's
+                       x_t and its density at the draft's x_{t-1} (Eq. 2).
+    In all three the token x_0 is the draft's and is shared (Eq. 4).
+
+    Returns (summary, dist2).  summary [R, 5D+1] has the layout of denoise_lockstep; its
+    last column is the log of the ratio over everything before the final step,
+      log p(x_T^p) - log q(x_T^q) + sum_{t=2..T} [log p(x^p_{t-1}|x^p_t) - log q(x^q_{t-1}|x^q_t)]
+    from the Gaussian densities themselves (Eq. 3; with x^p = x^q in the single-path mode),
+    so that log_ratio(), verify() and resample() apply unchanged.  dist2 [R] is
+    ||x^q_0 - x^p_0||^2 between the two heads' own final samples (the distance of the
+    alignment ablation; Theorem 1): x^p_0 = mu^p_1 + tau sigma^p_1 eps^p_1."""
+    assert mode in (RATIO_ALIGNED, RATIO_UNALIGNED, RATIO_SINGLE_PATH)
+    D, T = draft.cfg.token_dim, draft.cfg.n_steps
+    assert target.cfg.token_dim == D and target.cfg.n_steps == T
+    z_q = np.asarray(z_q, dtype=np.float64)
+    z_p = np.asarray(z_p, dtype=np.float64)
+    R = z_q.shape[0]
+    rows = row_offset + np.arange(R, dtype=np.uint64)
+    stream_p = STREAM_TRAJ_P if mode == RATIO_UNALIGNED else STREAM_TRAJ
+    e_q = draft.cond_embed(z_q)
+    e_p = target.cond_embed(z_p)
+    x_q = normals(seed, rows, T, STREAM_TRAJ, D)
+    x_p = normals(seed, rows, T, stream_p, D)
+    zero = np.zeros((R, D))
+    log_r = gaussian_logpdf(x_p, zero, zero) - gaussian_logpdf(x_q, zero, zero)   # 0 unless the starts differ
+    for t in range(T, 0, -1):
+        if mode == RATIO_SINGLE_PATH:
+            x_p = x_q                      # the target looks at the draft's state
+        eh_q, v_q = draft.forward(x_q, t, e_q)
+        eh_p, v_p = target.forward(x_p, t, e_p)
+        mu_q, lv_q = head_transition(draft, x_q, t, eh_q, v_q)
+        mu_p, lv_p = head_transition(target, x_p, t, eh_p, v_p)
+        xn_q = mu_q + tau * np.exp(0.5 * lv_q) * normals(seed, rows, t - 1, STREAM_TRAJ, D)
+        xn_p = mu_p + tau * np.exp(0.5 * lv_p) * normals(seed, rows, t - 1, stream_p, D)
+        if t >= 2:
+            at_p = xn_q if mode == RATIO_SINGLE_PATH else xn_p
+            log_r = log_r + gaussian_logpdf(at_p, mu_p, lv_p, tau) - gaussian_logpdf(xn_q, mu_q, lv_q, tau)
+            x_q, x_p = xn_q, xn_p
+        else:
+            summary = np.concatenate([mu_p, lv_p, mu_q, lv_q, xn_q, log_r[:, None]], axis=1)
+            return summary, np.sum((xn_q - xn_p) ** 2, axis=-1)
     raise AssertionError("T must be >= 1")
 
 

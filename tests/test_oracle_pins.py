@@ -281,8 +281,9 @@ def test_alignment_cancels_the_exponentials():
         assert np.allclose(ex["log_sigma_full"], summ[:, -1], rtol=1e-9, atol=1e-9)
         assert np.std(summ[:, -1]) > 1e-3        # not vacuous: variances differ
     # without alignment the exponentials do not cancel
-    summ, ex = O.denoise_lockstep(drf, tgt, zq, zp, seed=9, aligned=False)
-    assert not np.allclose(ex["log_sigma_full"], summ[:, -1], atol=1e-3)
+    su, _ = O.denoise_ablation(drf, tgt, zq, zp, seed=9, mode=O.RATIO_UNALIGNED)
+    half = 0.5 * (np.sum(su[:, 24:32], axis=1) - np.sum(su[:, 8:16], axis=1))        # final-step part only
+    assert np.std(su[:, -1]) > 10 * np.std(summ[:, -1]) and np.all(np.isfinite(half))
 
 
 def test_identical_heads_accept_everything():
@@ -336,10 +337,15 @@ def test_theorem1_alignment_gap():
         blob = S.head_weights(shape, 20 + k)
         _set(blob, shape, "out.w", 0.0)
         _set(blob, shape, "out.b", np.concatenate([np.full(8, eb), np.linspace(-1, 1, 8) * vb]))
-        heads.append(O.Head(O.HeadCfg(8, 6, 16, 1, 1), blob))
+        beta1 = O.Head(O.HeadCfg(8, 6, 16, 1, 1), blob).sched.beta[1]
+        # skip gain 1/beta_1 takes x_T out of mu_1, so the unaligned pair (whose x_T differ too) has the same means
+        heads.append(O.Head(O.HeadCfg(8, 6, 16, 1, 1, eps_skip_gain=1.0 / beta1), blob))
     z = np.zeros((R, 6))
-    _, ex_a = O.denoise_lockstep(heads[0], heads[1], z, z, seed=5, aligned=True)
-    _, ex_u = O.denoise_lockstep(heads[0], heads[1], z, z, seed=5, aligned=False)
+    _, ex_a = O.denoise_lockstep(heads[0], heads[1], z, z, seed=5)
+    _, d_a = O.denoise_ablation(heads[0], heads[1], z, z, seed=5, mode=O.RATIO_ALIGNED)
+    _, d_u = O.denoise_ablation(heads[0], heads[1], z, z, seed=5, mode=O.RATIO_UNALIGNED)
+    assert np.allclose(d_a, ex_a["dist2"], rtol=1e-12)
+    ex_u = dict(dist2=d_u)
     s = heads[0].sched
     sig = []
     for vb in (0.5, -0.4):
@@ -649,3 +655,115 @@ def test_guidance_special_cases_and_linearity():
     summ, _ = O.denoise_lockstep(g, g, zz, zz, seed=4)
     n_acc, ell, mask, _ = O.verify(summ, 6, 4, 4)
     assert np.all(ell == 0.0) and np.all(n_acc == 4)
+
+
+# ------------------------------------------- the three path ratios (Table 1) ----
+def _const_heads(T, gain=1.0):
+    """Two heads whose output layer has zero weights: eps_hat = eb + gain sqrt(1-abar_t) x_t and
+    v = vb are constants of the head, so every reverse step is an affine Gaussian map."""
+    shape = S.HeadShape(8, 6, 16, 1)
+    out = []
+    for k, (eb, vb) in enumerate([(0.3, 0.5), (-0.2, -0.4)]):          # target, draft
+        blob = S.head_weights(shape, 40 + k)
+        _set(blob, shape, "out.w", 0.0)
+        vbias = (np.linspace(-1, 1, 8) * vb).astype(np.float32).astype(np.float64)    # as the fp32 blob holds them
+        eb = float(np.float32(eb))
+        _set(blob, shape, "out.b", np.concatenate([np.full(8, eb), vbias]))
+        out.append((O.Head(O.HeadCfg(8, 6, 16, 1, T, eps_skip_gain=gain), blob), eb, vbias))
+    return out
+
+
+def _affine_step(h, eb, vbias, x, t, gain=1.0):
+    s = h.sched
+    a = (1 - gain * s.beta[t]) / math.sqrt(s.alpha[t])
+    c = s.beta[t] / math.sqrt(1 - s.abar[t]) / math.sqrt(s.alpha[t])
+    f = (vbias + 1) / 2
+    sd = np.exp(0.5 * (f * s.log_beta[t] + (1 - f) * s.log_beta_tilde_clip[t]))
+    return a * x - c * eb, np.broadcast_to(sd, x.shape)
+
+
+@pytest.mark.parametrize("mode", [O.RATIO_UNALIGNED, O.RATIO_SINGLE_PATH])
+def test_path_ratio_modes_on_affine_gaussian_chains(mode):
+    """With constant head outputs the paths are affine Gaussian chains: the ratio before the last
+    step and the token distance follow from scipy's normal log-density on a hand recursion."""
+    T, R, seed, off, tau = 5, 7, 31, 900, 0.9
+    (tgt, eb_p, vb_p), (drf, eb_q, vb_q) = _const_heads(T)
+    z = np.zeros((R, 6))
+    summ, dist2 = O.denoise_ablation(drf, tgt, z, z, seed, off, tau, mode)
+    rows = off + np.arange(R, dtype=np.uint64)
+    sp = O.STREAM_TRAJ_P if mode == O.RATIO_UNALIGNED else O.STREAM_TRAJ
+    xq = O.normals(seed, rows, T, O.STREAM_TRAJ, 8)
+    xp = O.normals(seed, rows, T, sp, 8)
+    want = stats.norm.logpdf(xp).sum(1) - stats.norm.logpdf(xq).sum(1)
+    for t in range(T, 0, -1):
+        if mode == O.RATIO_SINGLE_PATH:
+            xp = xq
+        mq, sq = _affine_step(drf, eb_q, vb_q, xq, t)
+        mp, sp_ = _affine_step(tgt, eb_p, vb_p, xp, t)
+        nq = mq + tau * sq * O.normals(seed, rows, t - 1, O.STREAM_TRAJ, 8)
+        np_ = mp + tau * sp_ * O.normals(seed, rows, t - 1, sp, 8)
+        if t >= 2:
+            at = nq if mode == O.RATIO_SINGLE_PATH else np_
+            want += stats.norm.logpdf(at, mp, tau * sp_).sum(1) - stats.norm.logpdf(nq, mq, tau * sq).sum(1)
+            xq, xp = nq, np_
+    assert np.allclose(summ[:, -1], want, rtol=1e-10, atol=1e-10)
+    assert np.allclose(summ[:, 0:8], mp) and np.allclose(summ[:, 16:24], mq) and np.allclose(summ[:, 32:40], nq)
+    assert np.allclose(dist2, ((nq - np_) ** 2).sum(1), rtol=1e-10)
+    assert np.abs(want).min() > 1e-3                                  # not vacuous
+
+
+def test_aligned_mode_is_the_lockstep_summary():
+    _, _, tgt, drf = _tiny_pair()
+    zq, zp = S.cond_vectors(16, 6, 3, add_std=0.3)
+    a, ex = O.denoise_lockstep(drf, tgt, zq, zp, seed=4, row_offset=77, tau=0.9)
+    b, d2 = O.denoise_ablation(drf, tgt, zq, zp, 4, 77, 0.9, O.RATIO_ALIGNED)
+    assert np.allclose(a, b, rtol=1e-9, atol=1e-9) and np.allclose(d2, ex["dist2"])
+
+
+def test_single_path_ratio_of_identical_heads_is_one():
+    _, _, tgt, drf = _tiny_pair(same=True)
+    z, _ = S.cond_vectors(12, 6, 5, add_std=0.0)
+    summ, d2 = O.denoise_ablation(drf, tgt, z, z, 3, 0, 1.0, O.RATIO_SINGLE_PATH)
+    assert np.all(summ[:, -1] == 0.0) and np.all(O.log_ratio(summ, 8) == 0.0) and np.all(d2 == 0.0)
+    # two independent paths of identical heads: the ratio is not one, it is the ratio of the noise densities
+    summ, d2 = O.denoise_ablation(drf, tgt, z, z, 3, 0, 1.0, O.RATIO_UNALIGNED)
+    assert np.std(summ[:, -1]) > 1.0 and np.all(d2 > 0)
+
+
+def test_single_path_ratio_has_unit_mean_under_the_draft():
+    """p(Y)/q(Y) with Y ~ q is an importance weight: its mean over draft paths is 1 (Eq. 2 with
+    both densities normalised).  Catches a dropped or mis-signed term of either density."""
+    shape = S.HeadShape(4, 6, 16, 1)
+    tb = S.head_weights(shape, 11, 0.3, 0.1)
+    db = S.perturbed_copy(tb, shape, 12, 0.02, 0.3)
+    cfg = O.HeadCfg(4, 6, 16, 1, 3)
+    tgt, drf = O.Head(cfg, tb), O.Head(cfg, db)
+    R = 200000
+    z = np.tile(S.cond_vectors(1, 6, 2, add_std=0.0)[0], (R, 1))
+    summ, _ = O.denoise_ablation(drf, tgt, z, z, 8, 0, 1.0, O.RATIO_SINGLE_PATH)
+    w = np.exp(O.log_ratio(summ, 4))
+    assert w.std() > 0.05                                             # the heads do differ
+    assert w.mean() == pytest.approx(1.0, abs=5 * w.std() / math.sqrt(R))
+
+
+def test_structure_of_the_ratio_comparison_on_synthetic_heads():
+    """What carries over from Table 1 and the alignment ablation to synthetic heads: alignment
+    raises the acceptance and shrinks the token distance by a wide margin; the single-path
+    log-ratio has negative mean (minus a KL divergence) that falls as the heads disagree more.
+    (Whether the single-path ratio is below the aligned one depends on the pair of heads.)"""
+    from tests import helpers as H
+    kl = []
+    for osc in (0.005, 0.02):
+        wl = S.WORKLOADS["tiny"].with_(draft=S.HeadShape(16, 64, 96, 2), n_steps=30, rho=0.9, out_scale=osc)
+        oq, op, _ = H.oracle_heads(wl)
+        zq, zp = wl.conds(128)
+        acc, dist, lr = {}, {}, {}
+        for mode in (O.RATIO_ALIGNED, O.RATIO_UNALIGNED, O.RATIO_SINGLE_PATH):
+            summ, d2 = O.denoise_ablation(oq, op, zq, zp, wl.seed, 0, 1.0, mode)
+            lr[mode] = O.log_ratio(summ, 16)
+            acc[mode] = np.mean(np.exp(np.minimum(lr[mode], 0.0)))
+            dist[mode] = d2.mean()
+        assert acc[O.RATIO_ALIGNED] > 100 * acc[O.RATIO_UNALIGNED]
+        assert dist[O.RATIO_ALIGNED] < 0.05 * dist[O.RATIO_UNALIGNED]
+        kl.append(-lr[O.RATIO_SINGLE_PATH].mean())
+    assert 0 < kl[0] < kl[1]
