@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--ddim-eta", type=float, default=None, help="use the DDIM sampler with this eta (default: DDPM)")
     ap.add_argument("--cfg-scale", type=float, default=None,
                     help="classifier-free guidance with this scale in both heads (two conditioning vectors per row)")
+    ap.add_argument("--ratio-mode", default=None, choices=[None, "aligned", "unaligned", "single_path"],
+                    help="form the path ratio as in the paper's comparison of calculation approaches "
+                         "(csd_denoise_ablation) instead of the method's lockstep call")
     ap.add_argument("--no-latency-shape", action="store_true", help="skip the split-phase latency-shape figure")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 256 MiB device to device once (a kernel of known "
@@ -93,11 +96,21 @@ def main():
         reps = 2
         a.no_latency_shape = True
     z_q, z_p = torch.from_numpy(zq_h[:R]).to(dev), torch.from_numpy(zp_h[:R]).to(dev)
-    ws = torch.empty(B.csd_workspace_bytes(h_q, h_p, R), dtype=torch.uint8, device=dev)
+    ratio_mode = {None: None, "aligned": B.CSD_RATIO_ALIGNED, "unaligned": B.CSD_RATIO_UNALIGNED,
+                  "single_path": B.CSD_RATIO_SINGLE_PATH}[a.ratio_mode]
+    n_ws = B.csd_workspace_bytes(h_q, h_p, R)
+    if ratio_mode is not None:
+        n_ws = max(n_ws, B.csd_ablation_workspace_bytes(h_q, h_p, R, ratio_mode))
+        a.no_latency_shape = True
+    ws = torch.empty(n_ws, dtype=torch.uint8, device=dev)
     summary = torch.empty((R, 5 * D + 1), dtype=torch.float32, device=dev)
+    dist2 = torch.empty((R,), dtype=torch.float32, device=dev)
 
     def step():
-        B.csd_denoise_lockstep(h_q, h_p, z_q, z_p, G, gamma, wl.seed, 0, 1.0, summary, ws)
+        if ratio_mode is None:
+            B.csd_denoise_lockstep(h_q, h_p, z_q, z_p, G, gamma, wl.seed, 0, 1.0, summary, ws)
+        else:
+            B.csd_denoise_ablation(h_q, h_p, z_q, z_p, G, gamma, wl.seed, 0, 1.0, ratio_mode, summary, dist2, ws)
         n_acc, ell, mask = B.csd_verify(summary, G, gamma, D, wl.seed)
         out = B.csd_resample(summary, n_acc, G, gamma, D, wl.seed)
         return n_acc, ell, mask, out
@@ -171,7 +184,7 @@ def main():
             wl.n_steps, R, G, gamma), "rows_per_step": R, "gamma": gamma, "out_scale": wl.out_scale,
             "eps_skip_gain": wl.eps_skip_gain,
             "sampler": "ddpm" if a.ddim_eta is None else "ddim(eta=%g)" % a.ddim_eta,
-            "cfg_scale": a.cfg_scale},
+            "cfg_scale": a.cfg_scale, "ratio_mode": a.ratio_mode},
         "wall_s": wall,
         "whole_path": {"algorithmic_TFLOP_per_s": flops_row * R * a.steps / (ms / 1e3) / 1e12,
                        "frac_of_peak": flops_row * R * a.steps / (ms / 1e3) / 1e12 / peak,
@@ -194,6 +207,13 @@ def main():
                                                                  "note": "same kernel and shapes, no other chain running"},
                      "traffic": measured_traffic(wl.name, dtype, R)},
     }
+
+    if ratio_mode is not None:
+        ell_h = ell.cpu().numpy().astype(np.float64)
+        res["ratio_comparison"] = {"mode": a.ratio_mode, "mean_log_ratio": float(ell_h.mean()),
+                                   "median_ratio": float(np.exp(np.median(ell_h))),
+                                   "row_accept_rate": float(mask_h.mean()),
+                                   "mean_token_distance2": float(dist2.double().mean().item())}
 
     # Secondary figure: one verify window the way an autoregressive loop runs Alg. 1 (split-phase
     # calls at the per-step shape: gamma draft calls of `batch` rows, one target call of batch*gamma
@@ -246,7 +266,10 @@ def main():
         o_q, o_p = O.Head(ocfg(ds), db), O.Head(ocfg(wl.target), tb)
         t_init = time.perf_counter() - t0
         t0 = time.perf_counter()
-        s_o, _ = O.denoise_lockstep(o_q, o_p, zq_h[:n], zp_h[:n], wl.seed)
+        if ratio_mode is None:
+            s_o, _ = O.denoise_lockstep(o_q, o_p, zq_h[:n], zp_h[:n], wl.seed)
+        else:
+            s_o, _ = O.denoise_ablation(o_q, o_p, zq_h[:n], zp_h[:n], wl.seed, 0, 1.0, ratio_mode)
         n_o, ell_o, mask_o, log_u = O.verify(s_o, n // gamma, gamma, wl.seed)
         O.resample(s_o, n_o, n // gamma, gamma, wl.seed)
         dt = time.perf_counter() - t0

@@ -67,6 +67,13 @@ extern "C" {
 #define CSD_STREAM_RESAMPLE_U  3  /* slot k: uniform of resampling trial k */
 #define CSD_STREAM_BONUS       4  /* trajectory noise of the target-only sample for position gamma+1;
                                     its "row" is the global GROUP index */
+#define CSD_STREAM_TRAJ_P      5  /* the target's own x_T and eps_t when the two paths are not aligned
+                                    (csd_denoise_ablation, CSD_RATIO_UNALIGNED); slots as in stream 0 */
+
+/* how csd_denoise_ablation forms the path ratio before the final step (Table 1) */
+#define CSD_RATIO_ALIGNED      0  /* p(Y_p)/q(Y_q) with eps^p_t = eps^q_t (Sec. 3.2): the method */
+#define CSD_RATIO_UNALIGNED    1  /* p(Y_p)/q(Y_q) with independent noise in the two paths (Eq. 4 alone) */
+#define CSD_RATIO_SINGLE_PATH  2  /* p(Y)/q(Y), both densities on the draft's path (Eq. 2) */
 
 /* bits of flags[g] written by csd_resample */
 #define CSD_FLAG_CAP        1u    /* max_trips reached; the last proposal was emitted */
@@ -165,6 +172,36 @@ int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target,
                          int64_t n_groups, int32_t gamma,
                          uint64_t seed, uint64_t row_offset, float temperature,
                          float* summary, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/*
+ * The comparison of ratio calculations (Table 1; the appendix on the approximation of
+ * the ratio) and the alignment ablation (the table of acceptance rate and token
+ * distance with and without alignment; Theorem 1).  Same arguments, layout and
+ * errors as csd_denoise_lockstep, plus:
+ *   ratio_mode  CSD_RATIO_ALIGNED: the lockstep path itself (the summary is bit-identical
+ *               to csd_denoise_lockstep's).  CSD_RATIO_UNALIGNED: the target draws its own
+ *               x_T^p and eps^p_t (stream CSD_STREAM_TRAJ_P); the exponents of the Gaussian
+ *               densities (Eq. 3) no longer cancel and are accumulated.  CSD_RATIO_SINGLE_PATH:
+ *               the target head is evaluated at the draft's x_t and its density at the
+ *               draft's x_{t-1} (Eq. 2).  In all modes x_0 is the draft's token (Eq. 4).
+ *   summary     [R, 5D+1] device, layout as in csd_denoise_lockstep; the last column is
+ *               log p(x_T^p) - log q(x_T^q) + sum_{t=2..T} [log p(x^p_{t-1}|x^p_t) -
+ *               log q(x^q_{t-1}|x^q_t)] (x^p = x^q in the single-path mode), so csd_verify
+ *               applies to it unchanged and gives that ratio's acceptance.
+ *   dist2       [R] device float, written: || x^q_0 - x^p_0 ||^2 with the target's own
+ *               final sample x^p_0 = mu^p_1 + tau sigma^p_1 eps^p_1.
+ *   workspace   csd_ablation_workspace_bytes(draft, target, R, ratio_mode) bytes, 256-byte
+ *               aligned; the single-path mode stores the draft's path there
+ *               ((T+1) R D floats).
+ * The single-path mode runs the draft's rows to the end before the target's.
+ */
+size_t csd_ablation_workspace_bytes(const csd_head_t* draft, const csd_head_t* target, int64_t n_rows,
+                                    int32_t ratio_mode);
+int csd_denoise_ablation(const csd_head_t* draft, const csd_head_t* target,
+                         const float* z_q, const float* z_p, int64_t n_groups, int32_t gamma,
+                         uint64_t seed, uint64_t row_offset, float temperature, int32_t ratio_mode,
+                         float* summary, float* dist2, void* workspace, size_t workspace_bytes,
                          void* hip_stream);
 
 /*

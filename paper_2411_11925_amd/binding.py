@@ -27,11 +27,13 @@ CSD_F32, CSD_BF16 = 0, 1
 CSD_COSINE, CSD_TABLE = 0, 1
 CSD_STREAM_TRAJ, CSD_STREAM_ACCEPT_U, CSD_STREAM_RESAMPLE_N, CSD_STREAM_RESAMPLE_U = 0, 1, 2, 3
 CSD_STREAM_BONUS = 4
+CSD_STREAM_TRAJ_P = 5
+CSD_RATIO_ALIGNED, CSD_RATIO_UNALIGNED, CSD_RATIO_SINGLE_PATH = 0, 1, 2
 CSD_SAMPLER_DDPM, CSD_SAMPLER_DDIM = 0, 1
 CSD_FLAG_CAP, CSD_FLAG_NONFINITE = 1, 2
 
 EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_set_guidance", "csd_workspace_bytes",
-           "csd_denoise_lockstep", "csd_denoise_draft", "csd_denoise_target", "csd_sample",
+           "csd_denoise_lockstep", "csd_ablation_workspace_bytes", "csd_denoise_ablation", "csd_denoise_draft", "csd_denoise_target", "csd_sample",
            "csd_verify", "csd_resample", "csd_append_bonus", "csd_head_eval",
            "csd_rng_normals", "csd_rng_uniforms", "csd_gemm_bf16", "csd_profile_enable", "csd_profile_read", "csd_last_error"]
 
@@ -59,6 +61,11 @@ _lib.csd_workspace_bytes.argtypes = [c_void_p, c_void_p, c_int64]
 _lib.csd_denoise_lockstep.restype = c_int
 _lib.csd_denoise_lockstep.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_uint64,
                                       c_uint64, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
+_lib.csd_ablation_workspace_bytes.restype = c_size_t
+_lib.csd_ablation_workspace_bytes.argtypes = [c_void_p, c_void_p, c_int64, c_int32]
+_lib.csd_denoise_ablation.restype = c_int
+_lib.csd_denoise_ablation.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_uint64,
+                                      c_uint64, c_float, c_int32, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
 _lib.csd_denoise_draft.restype = c_int
 _lib.csd_denoise_draft.argtypes = [c_void_p, c_void_p, c_int64, c_int32, c_int32, c_uint64, c_uint64, c_float,
                                    c_void_p, c_void_p, c_size_t, c_void_p]
@@ -200,6 +207,34 @@ def csd_denoise_lockstep(draft: Head, target: Head, z_q: torch.Tensor, z_p: torc
                                      seed, row_offset, temperature, _ptr(summary), _ptr(workspace),
                                      workspace.numel(), _stream(stream)))
     return summary
+
+
+def csd_ablation_workspace_bytes(draft: Head, target: Head, n_rows: int, ratio_mode: int) -> int:
+    return int(_lib.csd_ablation_workspace_bytes(draft.handle, target.handle, n_rows, ratio_mode))
+
+
+def csd_denoise_ablation(draft: Head, target: Head, z_q: torch.Tensor, z_p: torch.Tensor, n_groups: int,
+                         gamma: int, seed: int, row_offset: int, temperature: float, ratio_mode: int,
+                         summary: torch.Tensor | None = None, dist2: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None, stream=None):
+    """Returns (summary, dist2)."""
+    R, D = n_groups * gamma, draft.cfg.token_dim
+    assert z_q.is_cuda and z_p.is_cuda and z_q.dtype == torch.float32 and z_p.dtype == torch.float32
+    assert z_q.is_contiguous() and z_p.is_contiguous()
+    assert z_q.numel() == R * draft.reps * draft.cfg.cond_dim and z_p.numel() == R * target.reps * target.cfg.cond_dim
+    if summary is None:
+        summary = torch.empty((R, 5 * D + 1), dtype=torch.float32, device=z_q.device)
+    if dist2 is None:
+        dist2 = torch.empty((R,), dtype=torch.float32, device=z_q.device)
+    assert summary.is_contiguous() and tuple(summary.shape) == (R, 5 * D + 1) and summary.dtype == torch.float32
+    assert dist2.is_contiguous() and dist2.numel() == R and dist2.dtype == torch.float32
+    if workspace is None:
+        n = csd_ablation_workspace_bytes(draft, target, R, ratio_mode)
+        workspace = torch.empty(max(n, 256), dtype=torch.uint8, device=z_q.device)
+    _check(_lib.csd_denoise_ablation(draft.handle, target.handle, _ptr(z_q), _ptr(z_p), n_groups, gamma, seed,
+                                     row_offset, temperature, ratio_mode, _ptr(summary), _ptr(dist2), _ptr(workspace),
+                                     workspace.numel(), _stream(stream)))
+    return summary, dist2
 
 
 def csd_denoise_draft(draft: Head, z_q: torch.Tensor, n_groups: int, gamma: int, position: int, seed: int,

@@ -286,6 +286,10 @@ struct Chain {
     const csd_head* hd; HeadWs ws; const float* z; int64_t n;
     uint64_t row_offset; int64_t row_stride, row_shift; int rng_stream;
     float* summary; int is_target; float* tokens;
+    // path-ratio comparison (all zero in the method's own path): how acc is formed, the stored
+    // path [T+1][path_stride] floats (slot t holds x_t of this chain's rows) that the chain
+    // writes (path_write) or follows, whether acc starts at 1/2 ||x_T||^2, the own final sample
+    int path_mode; float* path; int64_t path_stride; int path_write; int init_norm; float* x0_own;
     hipStream_t s;
 };
 
@@ -317,8 +321,10 @@ int run_chains(Chain* chains, int n_chains, uint64_t seed, float tau, hipStream_
     const int T = chains[0].hd->T;
     for (int i = 0; i < n_chains; ++i) {
         Chain& ch = chains[i];
+        float* slot_T = ch.path ? ch.path + (int64_t)T * ch.path_stride : nullptr;
         HIP_TRY(launch_init_x(ch.ws.x, ch.ws.acc, ch.n, ch.hd->D, T, seed, ch.row_offset, ch.row_stride, ch.row_shift,
-                              ch.rng_stream, ch.s));
+                              ch.rng_stream, ch.init_norm, ch.path_write ? nullptr : slot_T,
+                              ch.path_write ? slot_T : nullptr, ch.s));
         HIP_TRY(cond_embed(ch.hd, ch.z, ch.ws, ch.n * ch.hd->reps, ch.s));
     }
     for (int t = T; t >= 1; --t) {
@@ -332,6 +338,11 @@ int run_chains(Chain* chains, int n_chains, uint64_t seed, float tau, hipStream_
             f.seed = seed; f.row_offset = ch.row_offset; f.tau = tau;
             f.row_stride = ch.row_stride; f.row_shift = ch.row_shift; f.rng_stream = ch.rng_stream;
             f.summary = ch.summary; f.is_target = ch.is_target; f.tokens = ch.tokens;
+            f.path_mode = ch.path_mode; f.x0_own = ch.x0_own;
+            if (ch.path && t >= 2) {
+                float* slot = ch.path + (int64_t)(t - 1) * ch.path_stride;
+                if (ch.path_write) f.path_out = slot; else f.path_in = slot;
+            }
             HIP_TRY(launch_transition(f, ch.s));
         }
     }
@@ -372,6 +383,68 @@ int run_single_head(const csd_head* hd, const float* z, int64_t n, uint64_t seed
     }
     *n_chains_out = n_chunks;
     return run_chains(chains, n_chunks, seed, tau, st, side);
+}
+
+// Both heads over the R rows of a call, cut into independent chains - (row chunk, head): rows
+// never interact, and the two heads only share the noise, which each regenerates from the
+// counters.  ratio_mode CSD_RATIO_ALIGNED is the method; the two others are the comparison
+// modes of Table 1.  In the single-path mode the target follows the draft's stored path, so the
+// draft's chains run to the end before the target's start.  x0_own (optional, [R,D]) takes the
+// target's own final sample.
+int run_pair(const csd_head* draft, const csd_head* target, const float* z_q, const float* z_p, int64_t R,
+             uint64_t seed, uint64_t row_offset, float tau, int ratio_mode, float* summary, float* x0_own,
+             float* path, char* wp, hipStream_t st) {
+    const int D = draft->D, T = draft->T;
+    SideStreams* side = side_streams(draft->device);
+    int64_t chunk_rows;
+    const int n_chunks = plan_chunks(R, side != nullptr, &chunk_rows);
+    Chain chains[8] = {};
+    int n_chains = 0;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t r0 = c * chunk_rows, n = (R - r0 < chunk_rows) ? R - r0 : chunk_rows;
+        for (int which = 0; which < 2; ++which) {
+            Chain& ch = chains[n_chains++];
+            ch.hd = which ? target : draft; ch.n = n; ch.z = (which ? z_p : z_q) + r0 * ch.hd->reps * ch.hd->C;
+            ch.row_offset = row_offset + (uint64_t)r0; ch.row_stride = 1; ch.row_shift = 0; ch.rng_stream = CSD_STREAM_TRAJ;
+            ch.summary = summary + r0 * (5 * D + 1); ch.is_target = which; ch.tokens = nullptr;
+            if (which && x0_own) ch.x0_own = x0_own + r0 * D;
+            if (ratio_mode == CSD_RATIO_UNALIGNED) {
+                ch.path_mode = PATH_OWN; ch.init_norm = 1;
+                if (which) ch.rng_stream = CSD_STREAM_TRAJ_P;
+            } else if (ratio_mode == CSD_RATIO_SINGLE_PATH) {
+                ch.path_mode = which ? PATH_FOLLOW : PATH_OWN;
+                ch.path = path + r0 * D; ch.path_stride = R * D; ch.path_write = !which;
+            }
+            wp = carve(ch.hd, n, steps_per_batch(ch.hd, R), wp, &ch.ws);
+        }
+    }
+    if (ratio_mode == CSD_RATIO_SINGLE_PATH) {
+        Chain half[4];
+        for (int which = 0; which < 2; ++which) {
+            for (int c = 0; c < n_chunks; ++c) half[c] = chains[2 * c + which];
+            int rc = run_chains(half, n_chunks, seed, tau, st, side);
+            if (rc != CSD_OK) return rc;
+        }
+    } else {
+        int rc = run_chains(chains, n_chains, seed, tau, st, side);
+        if (rc != CSD_OK) return rc;
+    }
+    (void)T;
+    const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
+    for (int i = 0; i < n_chains; i += 2)
+        HIP_TRY(launch_finish_summary(chains[i].summary, chains[i].ws.acc, chains[i + 1].ws.acc, ref_diff, chains[i].n, D,
+                                      0, 1, 0, st));
+    return CSD_OK;
+}
+
+int check_pair(const char* who, const csd_head* draft, const csd_head* target, int64_t n_groups, int gamma, float temperature) {
+    if (!draft || !target) return fail(CSD_EINVAL, "%s: NULL head", who);
+    if (n_groups < 0 || gamma < 1) return fail(CSD_EINVAL, "%s: n_groups >= 0 and gamma >= 1 required", who);
+    if (draft->D != target->D || draft->T != target->T || draft->device != target->device || draft->C != target->C)
+        return fail(CSD_EINVAL, "%s: heads must share token_dim, cond_dim, n_steps and device", who);
+    if (!(temperature > 0.f)) return fail(CSD_EINVAL, "%s: temperature must be > 0", who);
+    if (n_groups > (int64_t)(1 << 22) / gamma) return fail(CSD_EINVAL, "%s: more than 2^22 rows in one call", who);
+    return CSD_OK;
 }
 
 }  // namespace
@@ -600,46 +673,45 @@ size_t csd_workspace_bytes(const csd_head_t* draft, const csd_head_t* target, in
 int csd_denoise_lockstep(const csd_head_t* draft, const csd_head_t* target, const float* z_q, const float* z_p,
                          int64_t n_groups, int32_t gamma, uint64_t seed, uint64_t row_offset, float temperature,
                          float* summary, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!draft || !target) return fail(CSD_EINVAL, "csd_denoise_lockstep: NULL head");
-    if (n_groups < 0 || gamma < 1) return fail(CSD_EINVAL, "csd_denoise_lockstep: n_groups >= 0 and gamma >= 1 required");
-    if (draft->D != target->D || draft->T != target->T || draft->device != target->device || draft->C != target->C)
-        return fail(CSD_EINVAL, "csd_denoise_lockstep: heads must share token_dim, cond_dim, n_steps and device");
-    if (!(temperature > 0.f)) return fail(CSD_EINVAL, "csd_denoise_lockstep: temperature must be > 0");
-    if (n_groups > (int64_t)(1 << 22) / gamma) return fail(CSD_EINVAL, "csd_denoise_lockstep: more than 2^22 rows in one call");
+    int rc = check_pair("csd_denoise_lockstep", draft, target, n_groups, gamma, temperature);
+    if (rc != CSD_OK) return rc;
     const int64_t R = n_groups * gamma;
     if (R == 0) return CSD_OK;
-    if (!z_q || !z_p || !summary || !workspace) return fail(CSD_EINVAL, "csd_denoise_lockstep: NULL buffer");
-    if (((uintptr_t)workspace & 255u) != 0) return fail(CSD_EINVAL, "csd_denoise_lockstep: workspace must be 256-byte aligned");
-    if (workspace_bytes < csd_workspace_bytes(draft, target, R))
-        return fail(CSD_EINVAL, "csd_denoise_lockstep: workspace of %zu bytes, need %zu", workspace_bytes,
-                    csd_workspace_bytes(draft, target, R));
-    hipStream_t st = (hipStream_t)hip_stream;
-    const int D = draft->D;
-
-    // Rows never interact, and the two heads only share the noise (which each regenerates
-    // from the counters), so the call is cut into independent chains - (row chunk, head).
-    SideStreams* side = side_streams(draft->device);
-    int64_t chunk_rows;
-    const int n_chunks = plan_chunks(R, side != nullptr, &chunk_rows);
-    Chain chains[8];
-    int n_chains = 0;
-    char* wp_ = (char*)workspace;
-    for (int c = 0; c < n_chunks; ++c) {
-        const int64_t r0 = c * chunk_rows, n = (R - r0 < chunk_rows) ? R - r0 : chunk_rows;
-        for (int which = 0; which < 2; ++which) {
-            Chain& ch = chains[n_chains++];
-            ch.hd = which ? target : draft; ch.n = n; ch.z = (which ? z_p : z_q) + r0 * ch.hd->reps * ch.hd->C;
-            ch.row_offset = row_offset + (uint64_t)r0; ch.row_stride = 1; ch.row_shift = 0; ch.rng_stream = CSD_STREAM_TRAJ;
-            ch.summary = summary + r0 * (5 * D + 1); ch.is_target = which; ch.tokens = nullptr;
-            wp_ = carve(ch.hd, n, steps_per_batch(ch.hd, R), wp_, &ch.ws);
-        }
-    }
-    int rc = run_chains(chains, n_chains, seed, temperature, st, side);
+    if (!z_q || !z_p || !summary) return fail(CSD_EINVAL, "csd_denoise_lockstep: NULL buffer");
+    rc = check_ws("csd_denoise_lockstep", workspace, workspace_bytes, csd_workspace_bytes(draft, target, R));
     if (rc != CSD_OK) return rc;
-    const float ref_diff = (float)(draft->ref_log_sigma - target->ref_log_sigma);
-    for (int i = 0; i < n_chains; i += 2)
-        HIP_TRY(launch_finish_summary(chains[i].summary, chains[i].ws.acc, chains[i + 1].ws.acc, ref_diff, chains[i].n, D,
-                                      0, 1, 0, st));
+    return run_pair(draft, target, z_q, z_p, R, seed, row_offset, temperature, CSD_RATIO_ALIGNED, summary, nullptr,
+                    nullptr, (char*)workspace, (hipStream_t)hip_stream);
+}
+
+size_t csd_ablation_workspace_bytes(const csd_head_t* draft, const csd_head_t* target, int64_t n_rows, int32_t ratio_mode) {
+    if (n_rows < 0 || !draft || !target) return 0;
+    size_t n = csd_workspace_bytes(draft, target, n_rows) + align_up((size_t)n_rows * draft->D * 4, 256);
+    if (ratio_mode == CSD_RATIO_SINGLE_PATH) n += align_up((size_t)(draft->T + 1) * n_rows * draft->D * 4, 256);
+    return n;
+}
+
+int csd_denoise_ablation(const csd_head_t* draft, const csd_head_t* target, const float* z_q, const float* z_p,
+                         int64_t n_groups, int32_t gamma, uint64_t seed, uint64_t row_offset, float temperature,
+                         int32_t ratio_mode, float* summary, float* dist2, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+    int rc = check_pair("csd_denoise_ablation", draft, target, n_groups, gamma, temperature);
+    if (rc != CSD_OK) return rc;
+    if (ratio_mode != CSD_RATIO_ALIGNED && ratio_mode != CSD_RATIO_UNALIGNED && ratio_mode != CSD_RATIO_SINGLE_PATH)
+        return fail(CSD_EINVAL, "csd_denoise_ablation: unknown ratio_mode %d", (int)ratio_mode);
+    const int64_t R = n_groups * gamma;
+    if (R == 0) return CSD_OK;
+    if (!z_q || !z_p || !summary || !dist2) return fail(CSD_EINVAL, "csd_denoise_ablation: NULL buffer");
+    rc = check_ws("csd_denoise_ablation", workspace, workspace_bytes, csd_ablation_workspace_bytes(draft, target, R, ratio_mode));
+    if (rc != CSD_OK) return rc;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* wp = (char*)workspace;
+    float* x0_own = (float*)wp; wp += align_up((size_t)R * draft->D * 4, 256);
+    float* path = nullptr;
+    if (ratio_mode == CSD_RATIO_SINGLE_PATH) { path = (float*)wp; wp += align_up((size_t)(draft->T + 1) * R * draft->D * 4, 256); }
+    rc = run_pair(draft, target, z_q, z_p, R, seed, row_offset, temperature, ratio_mode, summary, x0_own, path, wp, st);
+    if (rc != CSD_OK) return rc;
+    HIP_TRY(launch_token_distance(summary, x0_own, dist2, R, draft->D, st));
     return CSD_OK;
 }
 
@@ -656,7 +728,7 @@ int csd_denoise_draft(const csd_head_t* draft, const float* z_q, int64_t n_group
     int rc = check_ws("csd_denoise_draft", workspace, workspace_bytes, csd_workspace_bytes(draft, nullptr, n_groups));
     if (rc != CSD_OK) return rc;
     hipStream_t st = (hipStream_t)hip_stream;
-    Chain chains[8];
+    Chain chains[8] = {};
     int n_chains = 0;
     rc = run_single_head(draft, z_q, n_groups, seed, row_offset, gamma, position, CSD_STREAM_TRAJ, temperature, summary, 0,
                          nullptr, workspace, st, chains, &n_chains);
@@ -682,7 +754,7 @@ int csd_denoise_target(const csd_head_t* target, const csd_head_t* draft, const 
     int rc = check_ws("csd_denoise_target", workspace, workspace_bytes, csd_workspace_bytes(nullptr, target, R));
     if (rc != CSD_OK) return rc;
     hipStream_t st = (hipStream_t)hip_stream;
-    Chain chains[8];
+    Chain chains[8] = {};
     int n_chains = 0;
     rc = run_single_head(target, z_p, R, seed, row_offset, 1, 0, CSD_STREAM_TRAJ, temperature, summary, 1, nullptr,
                          workspace, st, chains, &n_chains);
@@ -706,7 +778,7 @@ int csd_sample(const csd_head_t* head, const float* z, int64_t n_rows, uint64_t 
     if (!z || !tokens) return fail(CSD_EINVAL, "csd_sample: NULL buffer");
     int rc = check_ws("csd_sample", workspace, workspace_bytes, csd_workspace_bytes(head, nullptr, n_rows));
     if (rc != CSD_OK) return rc;
-    Chain chains[8];
+    Chain chains[8] = {};
     int n_chains = 0;
     return run_single_head(head, z, n_rows, seed, row_offset, 1, 0, rng_stream, temperature, nullptr, 0, tokens, workspace,
                            (hipStream_t)hip_stream, chains, &n_chains);

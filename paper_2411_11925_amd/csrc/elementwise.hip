@@ -325,13 +325,24 @@ __global__ void k_transition(TransArgs a) {
     const float eps = nrm[d & 3];
     const float lv = fmaf(o_v, a.coef.lhalf, a.coef.lmid);
     const float mu = fmaf(a.coef.cx, x, -a.coef.co * o_eps);
-    const float xn = fmaf(a.tau * expf(0.5f * lv), eps, mu);
+    const float sd = a.tau * expf(0.5f * lv);
+    float xn = fmaf(sd, eps, mu);
     if (a.t >= 2) {
-        a.x[r * D + d] = xn;
         float vs = o_v;                       // sum_d v_d over the D lanes of the row
 #pragma unroll
         for (int o = D / 2; o >= 1; o >>= 1) vs += __shfl_xor(vs, o, 64);
-        if (d == 0) a.acc[r] += 0.5f * a.coef.lhalf * vs;
+        float add = 0.5f * a.coef.lhalf * vs;
+        if (a.path_mode != PATH_PLAIN) {      // the exponent of this step's density (uniform over the launch)
+            float q = eps;
+            if (a.path_mode == PATH_FOLLOW) { xn = a.path_in[r * D + d]; q = (xn - mu) / sd; }
+            q *= q;
+#pragma unroll
+            for (int o = D / 2; o >= 1; o >>= 1) q += __shfl_xor(q, o, 64);
+            add += 0.5f * q;
+        }
+        a.x[r * D + d] = xn;
+        if (a.path_out) a.path_out[r * D + d] = xn;
+        if (d == 0) a.acc[r] += add;
     } else if (a.tokens) {
         a.tokens[r * D + d] = xn;             // plain sampling: x_0 itself
     } else {
@@ -341,6 +352,7 @@ __global__ void k_transition(TransArgs a) {
         } else {
             srow[2 * D + d] = mu; srow[3 * D + d] = lv; srow[4 * D + d] = xn;
         }
+        if (a.x0_own) a.x0_own[r * D + d] = xn;
     }
 }
 
@@ -359,24 +371,55 @@ hipError_t launch_transition(const TransArgs& a, hipStream_t st) {
 
 // ---------------------------------------------------------------- x_T = eps_T, accumulator = 0
 __global__ void k_init_x(float* __restrict__ x, float* __restrict__ acc, int64_t R, int D, int T, uint64_t seed,
-                         uint64_t row_offset, int64_t row_stride, int64_t row_shift, int rng_stream) {
+                         uint64_t row_offset, int64_t row_stride, int64_t row_shift, int rng_stream, int acc_norm,
+                         const float* __restrict__ x_src, float* __restrict__ x_store) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // one thread per (row, block of 4)
     const int nb = D >> 2;
-    if (i >= R * nb) return;
+    if (i >= R * nb) return;                   // the nb lanes of a row drop out together
     const int64_t r = i / nb; const int b = (int)(i % nb);
     float n[4];
-    normals4(seed, row_offset + (uint64_t)(r * row_stride + row_shift), (uint32_t)T, (uint32_t)rng_stream, (uint32_t)b, n);
+    if (x_src) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) x[r * D + 4 * b + j] = n[j];
-    if (b == 0) acc[r] = 0.f;
+        for (int j = 0; j < 4; ++j) n[j] = x_src[r * D + 4 * b + j];
+    } else {
+        normals4(seed, row_offset + (uint64_t)(r * row_stride + row_shift), (uint32_t)T, (uint32_t)rng_stream, (uint32_t)b, n);
+    }
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        x[r * D + 4 * b + j] = n[j];
+        if (x_store) x_store[r * D + 4 * b + j] = n[j];
+        q = fmaf(n[j], n[j], q);
+    }
+    for (int o = nb / 2; o >= 1; o >>= 1) q += __shfl_xor(q, o, 64);      // nb is 1, 2 or 4
+    if (b == 0) acc[r] = acc_norm ? 0.5f * q : 0.f;
 }
 
 hipError_t launch_init_x(float* x, float* acc, int64_t R, int D, int T, uint64_t seed, uint64_t row_offset,
-                         int64_t row_stride, int64_t row_shift, int rng_stream, hipStream_t st) {
+                         int64_t row_stride, int64_t row_shift, int rng_stream, int acc_norm, const float* x_src,
+                         float* x_store, hipStream_t st) {
     const int64_t n = R * (D >> 2);
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(k_init_x, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, acc, R, D, T, seed, row_offset,
-                       row_stride, row_shift, rng_stream);
+                       row_stride, row_shift, rng_stream, acc_norm, x_src, x_store);
+    return hipGetLastError();
+}
+
+// squared distance between the draft token of a summary row and the target's own final sample
+__global__ void k_token_distance(const float* __restrict__ summary, const float* __restrict__ x0_own,
+                                 float* __restrict__ dist2, int64_t R, int D) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= R) return;
+    const float* x0 = summary + r * (5 * D + 1) + 4 * D;
+    float q = 0.f;
+    for (int d = 0; d < D; ++d) { const float df = x0[d] - x0_own[r * D + d]; q = fmaf(df, df, q); }
+    dist2[r] = q;
+}
+
+hipError_t launch_token_distance(const float* summary, const float* x0_own, float* dist2, int64_t R, int D,
+                                 hipStream_t st) {
+    if (R == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_token_distance, dim3((unsigned)((R + 255) / 256)), dim3(256), 0, st, summary, x0_own, dist2, R, D);
     return hipGetLastError();
 }
 

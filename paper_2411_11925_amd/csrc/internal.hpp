@@ -131,11 +131,25 @@ struct TransArgs {
     float skip_coef;           // eps_skip_gain * sqrt(1 - abar_t), for raw_out only
     int reps; float cfg_scale; // reps == 2: row r's outputs are o[2r] (conditional) and o[2r+1] (unconditional);
                                // eps part = o_u + cfg_scale (o_c - o_u), v part = the conditional one
+    // Path-ratio comparison (Table 1).  PATH_PLAIN: acc takes the log-variance part only (under aligned
+    // noise the exponents of the two heads' densities cancel, Eq. 6).  PATH_OWN: acc also takes
+    // 1/2 ||eps_t||^2, the exponent of this head's density at its own sample.  PATH_FOLLOW: the head does
+    // not sample; x_{t-1} is read from path_in and acc takes 1/2 ||(x_{t-1} - mu)/(tau sigma)||^2 (Eq. 2).
+    int path_mode;
+    const float* path_in;      // [R,D] x_{t-1} of the path to follow (PATH_FOLLOW, t >= 2)
+    float* path_out;           // optional [R,D]: x_{t-1} is also stored here (t >= 2)
+    float* x0_own;             // optional [R,D]: at t = 1 the head's own sample mu_1 + tau sigma_1 eps_1
 };
+enum { PATH_PLAIN = 0, PATH_OWN = 1, PATH_FOLLOW = 2 };
 hipError_t launch_transition(const TransArgs& a, hipStream_t st);
 
+// x = eps_T from the counters (or a copy of x_src), acc = 0 (or 1/2 ||x_T||^2 if acc_norm), x_store (optional) = x
 hipError_t launch_init_x(float* x, float* acc, int64_t R, int D, int T, uint64_t seed, uint64_t row_offset,
-                         int64_t row_stride, int64_t row_shift, int rng_stream, hipStream_t st);
+                         int64_t row_stride, int64_t row_shift, int rng_stream, int acc_norm, const float* x_src,
+                         float* x_store, hipStream_t st);
+// dist2[r] = || x_0 of summary row r - x0_own[r] ||^2
+hipError_t launch_token_distance(const float* summary, const float* x0_own, float* dist2, int64_t R, int D,
+                                 hipStream_t st);
 // mode 0: lockstep (acc_q - acc_p + ref); 1: draft phase parks acc_q; 2: target phase finishes from the parked value
 hipError_t launch_finish_summary(float* summary, const float* accq, const float* accp, float ref_diff,
                                  int64_t R, int D, int mode, int64_t row_stride, int64_t row_shift, hipStream_t st);

@@ -73,4 +73,7 @@ def test_argument_errors_without_device_work(B):
     assert lib.csd_append_bonus(None, None, None, None, 4, 4, 16, None) == B.CSD_EINVAL      # NULL buffers
     assert lib.csd_append_bonus(None, None, None, None, 0, 4, 16, None) == B.CSD_OK          # empty: no-op
     assert lib.csd_workspace_bytes(None, None, 10) == 0
+    assert lib.csd_ablation_workspace_bytes(None, None, 10, 2) == 0
+    assert lib.csd_denoise_ablation(None, None, None, None, 1, 1, 0, 0, 1.0, 0, None, None, None, 0, None) == B.CSD_EINVAL
+    assert b"NULL head" in lib.csd_last_error()
     lib.csd_free_head(None)
