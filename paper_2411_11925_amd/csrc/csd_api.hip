@@ -93,7 +93,7 @@ size_t head_ws_bytes(const csd_head* hd, int64_t R, int tb) {
     n += align_up(r * W * 4, 256);          // h
     n += align_up(r * W * 4, 256);          // u (fp32, bf16, or the [hi|lo] bf16 pair of the last layer)
     n += 2 * align_up(r * W * act, 256);    // a, y
-    n += align_up(r * 64 * 4, 256);         // o (output projection, padded to 64 columns)
+    n += align_up(r * 64 * 4 * hd->out_splits, 256);   // o (output projection, padded to 64 columns; split-K partials)
     n += align_up((size_t)R * hd->D * 4, 256);      // x
     n += align_up((size_t)R * 4, 256);              // acc
     return n;
@@ -111,7 +111,7 @@ char* carve(const csd_head* hd, int64_t R, int tb, char* p, HeadWs* ws) {
     ws->u = take(r * W * 4);
     ws->a = take(r * W * act);
     ws->y = take(r * W * act);
-    ws->o = (float*)take(r * 64 * 4);
+    ws->o = (float*)take(r * 64 * 4 * hd->out_splits);
     ws->x = (float*)take((size_t)R * hd->D * 4);
     ws->acc = (float*)take((size_t)R * 4);
     return p;
@@ -187,6 +187,9 @@ hipError_t phase_gemm(const csd_head* hd, const HeadWs& ws, int p, int64_t R, hi
         g.N = 64; g.K = b16 ? 2 * W : W; g.A = ws.u; g.lda = g.K;
         g.B = b16 ? (const void*)hd->out_pad.w16 : (const void*)hd->out_pad.w; g.bias = hd->out_pad.b;
         g.C = ws.o; g.ldc = 64; g.epi = EPI_BIAS; g.c_is_f32 = 1;
+        // a 64-column output has few tiles and a long K: cut K so that the launch is not one long
+        // dependent chain per workgroup; the transition adds the partial products
+        g.k_splits = hd->out_splits; g.c_split_stride = (int64_t)R * 64;
         return gemm(hd, g, sg);
     }
     if (p >= 1) {
@@ -232,6 +235,7 @@ hipError_t head_body(const csd_head* hd, const HeadWs& ws, int k, int64_t R, hip
 TransArgs trans_args(const csd_head* hd, const HeadWs& ws, int t, int64_t R) {
     TransArgs f{};
     f.o = ws.o; f.ldo = 64; f.R = R; f.D = hd->D; f.x = ws.x; f.acc = ws.acc;
+    f.o_splits = hd->out_splits; f.o_split_stride = (int64_t)R * hd->reps * 64;
     f.coef = hd->coef[t]; f.t = t;
     f.row_stride = 1; f.row_shift = 0; f.rng_stream = CSD_STREAM_TRAJ;
     f.reps = hd->reps; f.cfg_scale = hd->cfg_scale;
@@ -611,6 +615,10 @@ int csd_init_head(const csd_head_cfg_t* cfg, const float* weights_host, size_t n
         INIT_TRY(launch_f32_to_bf16_rows(h->out_pad.w, dst, 64, W, 2 * W, nullptr));
         INIT_TRY(launch_f32_to_bf16_rows(h->out_pad.w, dst + W, 64, W, 2 * W, nullptr));
         h->out_pad.w16 = dst;
+        // K = 2W of the output projection in 4 ranges where each is a whole number of 64-wide slabs
+        const char* e = getenv("CSD_OUT_SPLITS");
+        const int want = (e && *e) ? atoi(e) : 4;
+        h->out_splits = (want >= 1 && want <= 8 && (2 * W) % (64 * want) == 0 && 2 * W >= 1024) ? want : 1;
     }
 
     // ---- the L modulation layers stacked into one [L*3W, W] matrix: they all read the same

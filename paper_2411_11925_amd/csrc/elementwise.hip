@@ -37,18 +37,6 @@ __global__ void k_cond_silu(const float* __restrict__ e, const float* __restrict
     }
 }
 
-hipError_t launch_cond_silu(const float* e, const float* temb_first, int n_steps, void* s, int act, int64_t R, int W,
-                            hipStream_t st) {
-    const size_t n_one = (size_t)R * W, n = n_one * (size_t)n_steps;
-    if (n == 0) return hipSuccess;
-    const int threads = 256;
-    const size_t want = (n + threads - 1) / threads;
-    const int blocks = (int)(want < 16384 ? want : 16384);
-    if (act == ACT_BF16) hipLaunchKernelGGL(k_cond_silu<bf16_t>, dim3(blocks), dim3(threads), 0, st, e, temb_first, (bf16_t*)s, n_one, n_steps, W);
-    else hipLaunchKernelGGL(k_cond_silu<float>, dim3(blocks), dim3(threads), 0, st, e, temb_first, (float*)s, n_one, n_steps, W);
-    return hipGetLastError();
-}
-
 // ---------------------------------------------------------------- start of a block
 // One wave per row, the row held in registers, one pass over memory:
 //   FIRST : h = W_in x + b_in                      (input projection of the head)
@@ -75,6 +63,51 @@ template <> __device__ __forceinline__ void store4<float>(float* p, const float 
 }
 template <> __device__ __forceinline__ void store4<bf16_t>(bf16_t* p, const float v[4]) {
     *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+}
+
+// Vector form (W % 4 == 0): a workgroup takes 8 rows of one step, a thread 4 consecutive
+// columns, so the 16 bytes of the time embedding are loaded once for the 8 rows and the index
+// arithmetic has no division.  Same operations per element as the scalar kernel.
+template <typename TAct>
+__global__ __launch_bounds__(256) void k_cond_silu_v4(const float* __restrict__ e, const float* __restrict__ temb,
+                                                     TAct* __restrict__ s, int64_t R, int W) {
+    constexpr int ROWS = 8;
+    const int64_t r0 = (int64_t)blockIdx.x * ROWS;
+    const int k = blockIdx.y;
+    const float* trow = temb - (ptrdiff_t)k * W;
+    TAct* sk = s + (size_t)k * (size_t)R * W;
+    for (int c = threadIdx.x * 4; c < W; c += 256 * 4) {
+        float t4[4];
+        load4<float>(trow + c, t4);
+#pragma unroll
+        for (int rr = 0; rr < ROWS; ++rr) {
+            const int64_t r = r0 + rr;
+            if (r >= R) break;
+            float e4[4], v[4];
+            load4<float>(e + r * W + c, e4);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = silu_f(e4[q] + t4[q]);
+            store4<TAct>(sk + r * W + c, v);
+        }
+    }
+}
+
+hipError_t launch_cond_silu(const float* e, const float* temb_first, int n_steps, void* s, int act, int64_t R, int W,
+                            hipStream_t st) {
+    const size_t n_one = (size_t)R * W, n = n_one * (size_t)n_steps;
+    if (n == 0) return hipSuccess;
+    if (W % 4 == 0 && n_steps <= 65535 && (((uintptr_t)e | (uintptr_t)temb_first | (uintptr_t)s) & 15u) == 0) {
+        dim3 grid((unsigned)((R + 7) / 8), (unsigned)n_steps), block(256);
+        if (act == ACT_BF16) hipLaunchKernelGGL(k_cond_silu_v4<bf16_t>, grid, block, 0, st, e, temb_first, (bf16_t*)s, R, W);
+        else hipLaunchKernelGGL(k_cond_silu_v4<float>, grid, block, 0, st, e, temb_first, (float*)s, R, W);
+        return hipGetLastError();
+    }
+    const int threads = 256;
+    const size_t want = (n + threads - 1) / threads;
+    const int blocks = (int)(want < 16384 ? want : 16384);
+    if (act == ACT_BF16) hipLaunchKernelGGL(k_cond_silu<bf16_t>, dim3(blocks), dim3(threads), 0, st, e, temb_first, (bf16_t*)s, n_one, n_steps, W);
+    else hipLaunchKernelGGL(k_cond_silu<float>, dim3(blocks), dim3(threads), 0, st, e, temb_first, (float*)s, n_one, n_steps, W);
+    return hipGetLastError();
 }
 
 // NCH = W / 256 chunks of 4 consecutive features per lane (fast path); NCH = 0: any W % 64 == 0,
@@ -307,10 +340,16 @@ __global__ void k_transition(TransArgs a) {
     const int d = (int)(i % D);
     if (r >= a.R) return;                      // whole D-lane segments drop out together
     const int64_t ro = r * a.reps;
+    // the output projection arrives as o_splits partial products (split-K), added here in order
     float o_eps = a.o[ro * a.ldo + d];
-    const float o_v = a.o[ro * a.ldo + D + d];
+    float o_v = a.o[ro * a.ldo + D + d];
+    for (int s = 1; s < a.o_splits; ++s) {
+        o_eps += a.o[s * a.o_split_stride + ro * a.ldo + d];
+        o_v += a.o[s * a.o_split_stride + ro * a.ldo + D + d];
+    }
     if (a.reps == 2) {                         // classifier-free guidance: eps_u + s (eps_c - eps_u)
-        const float o_u = a.o[(ro + 1) * a.ldo + d];
+        float o_u = a.o[(ro + 1) * a.ldo + d];
+        for (int s = 1; s < a.o_splits; ++s) o_u += a.o[s * a.o_split_stride + (ro + 1) * a.ldo + d];
         o_eps = fmaf(a.cfg_scale, o_eps - o_u, o_u);
     }
     const float x = a.x[r * D + d];

@@ -44,6 +44,8 @@ struct Params {
     int M, N, K;
     int tiles_m, tiles_n;
     int panel;                  // > 0: an XCD walks its tiles in column panels of this many N-tiles
+    int ksplit;                 // length of the K range of one workgroup row (gridDim.y ranges; = K without split-K)
+    long long c_split_stride;   // elements between the partial products of consecutive K ranges
     unsigned long long* ts;     // optional: [0] min start, [1] max end over the workgroups (profiling)
 };
 
@@ -94,6 +96,9 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     }
     const int64_t m0 = (int64_t)tm * BM;
     const int n0 = tn * BN;
+    // split-K: workgroup row blockIdx.y sums its own K range into its own copy of C
+    const bf16_t* const Ap = p.A + (size_t)blockIdx.y * p.ksplit;
+    const bf16_t* const Bp = p.B + (size_t)blockIdx.y * p.ksplit;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -113,9 +118,9 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
             if (g < BM / RPL) {                        // uniform per wave and i
                 int64_t r = m0 + row;
                 r = r < p.M ? r : (int64_t)p.M - 1;
-                src = p.A + r * p.lda + k0 + ld_chunk * 8;
+                src = Ap + r * p.lda + k0 + ld_chunk * 8;
             } else {
-                src = p.B + (size_t)(n0 + row - BM) * p.K + k0 + ld_chunk * 8;
+                src = Bp + (size_t)(n0 + row - BM) * p.K + k0 + ld_chunk * 8;
             }
             __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void*)(smem + stage * STAGE_B + g * 1024),
                                              16, 0, 0);
@@ -139,7 +144,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int nk = p.K / BK;
+    const int nk = p.ksplit / BK;
     if constexpr (PIPE) {
         // ---- software-pipelined main loop (two stages of 64, at least 4 slabs).  Fragments are
         // double-buffered in registers, so the LDS reads of k16-step kk+1 run under the MFMAs of
@@ -274,6 +279,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     // one store round trip at a time.
     const int n_ep = n0 + wn * TN + (rd_c < NCH ? rd_c : 0) * 4;
     float4 bb = *reinterpret_cast<const float4*>(p.bias + n_ep);
+    if (blockIdx.y != 0) bb = make_float4(0.f, 0.f, 0.f, 0.f);       // the bias goes into the first K range only
     asm volatile("" : "+v"(bb.x), "+v"(bb.y), "+v"(bb.z), "+v"(bb.w));
     // Tiles that lie wholly inside M take the copy of the code without row guards, where the
     // compiler is free to batch the LDS reads and stores of a slab.
@@ -309,7 +315,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
                     v3 = fmaf(bf16_to_f32((bf16_t)(g.y >> 16)), v3, c.w);
                     *reinterpret_cast<float4*>(cp) = make_float4(v0, v1, v2, v3);
                 } else if (OUT_F32) {
-                    *reinterpret_cast<float4*>((float*)p.C + m * p.ldc + n) = make_float4(v0, v1, v2, v3);
+                    *reinterpret_cast<float4*>((float*)p.C + (size_t)blockIdx.y * p.c_split_stride + m * p.ldc + n) = make_float4(v0, v1, v2, v3);
                 } else {
                     *reinterpret_cast<uint2*>((bf16_t*)p.C + m * p.ldc + n) =
                         make_uint2(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3));
@@ -327,13 +333,17 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t st) {
     p.A = (const bf16_t*)g.A; p.lda = g.lda; p.B = (const bf16_t*)g.B; p.bias = g.bias;
     p.C = g.C; p.ldc = g.ldc; p.gate = (const bf16_t*)g.gate; p.ldg = g.ldg;
     p.M = g.M; p.N = g.N; p.K = g.K; p.ts = g.ts;
+    const int splits = g.k_splits > 1 ? g.k_splits : 1;
+    // split-K: fp32 partial products only (plain bias epilogue), each range a whole number of slabs
+    if (splits > 1 && (g.epi != EPI_BIAS || !g.c_is_f32 || g.K % (splits * BK) != 0 || PIPE)) return hipErrorInvalidValue;
+    p.ksplit = g.K / splits; p.c_split_stride = g.c_split_stride;
     p.tiles_m = (g.M + BM - 1) / BM; p.tiles_n = g.N / BN;
     p.panel = 0;
     if (p.tiles_n > 16)
         for (int d = 16; d >= 8; --d)
             if (p.tiles_n % d == 0) { p.panel = d; break; }
     const size_t smem = (size_t)NST * (BM + BN) * BK * 2;
-    dim3 grid((unsigned)(p.tiles_m * p.tiles_n)), block(WM * WN * 64);
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), (unsigned)splits), block(WM * WN * 64);
 #define CSD_LAUNCH(EPI, F32)                                                                                   \
     do {                                                                                                       \
         auto kern = k_gemm_bf16<BM, BN, WM, WN, BK, NST, EPI, F32, PIPE>;                                            \
@@ -384,6 +394,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
         else if (g.M >= 2048 && g.N % 192 == 0) variant = 8;
         else variant = 3;
     }
+    if (g.k_splits > 1) variant = 3;
     if ((variant == 1 || variant == 9) && g.N % 256 != 0) variant = (g.N % 192 == 0) ? 8 : 3;
     if (variant == 8 && g.N % 192 != 0) variant = 3;
     switch (variant) {

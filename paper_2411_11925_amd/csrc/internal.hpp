@@ -56,6 +56,8 @@ struct csd_head {
     float cfg_scale = 0.f;               // guidance scale (reps == 2)
     csd::Linear t1, t2, cond, in, fmod, out;
     csd::Linear out_pad;                 // output layer padded to 64 rows; bf16 copy is [w | w] (2W per row)
+    int out_splits = 1;                  // K ranges of the output projection (a fixed property of the head, so that
+                                         // every call shape adds the same partial sums in the same order)
     float* d_out_pad = nullptr;          // storage of out_pad (fp32 w, b)
     float* d_in_t = nullptr;             // input projection transposed to [D, W]
     std::vector<csd::Linear> mod, fc1, fc2;
@@ -89,6 +91,9 @@ struct GemmArgs {
     int M, N, K;
     int epi;
     int c_is_f32;                  // output type override: 1 = fp32 even in bf16 mode
+    int k_splits;                  // bf16 kernels: > 1 cuts K into that many equal ranges (K % (64 k_splits) == 0); range
+    int64_t c_split_stride;        // s writes its partial product to C + s * c_split_stride elements, the bias goes
+                                   // into range 0 only; the consumer adds the partials.  0 or 1: off
     unsigned long long* ts;        // optional, device: ts[0] = min start, ts[1] = max end of the workgroups (100 MHz
                                    // constant clock), for profiling; bf16 kernels only
 };
@@ -117,6 +122,7 @@ hipError_t launch_block_pre(const BlockPreArgs& a, hipStream_t st);
 
 struct TransArgs {
     const float* o; int ldo;   // [R, ldo] fp32 output projection: columns [0,D) eps part, [D,2D) v
+    int o_splits; int64_t o_split_stride;   // o is the sum of o_splits partial products, o_split_stride floats apart
     int64_t R; int D;
     float* x;                  // [R,D] in: x_t, out: x_{t-1} (not written at t = 1)
     float* acc;                // [R] running 1/2 sum_d (log sigma^2 - lmid_t), t >= 2
