@@ -380,7 +380,12 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
     if (((uintptr_t)g.A & 15u) || ((uintptr_t)g.B & 15u) || ((uintptr_t)g.C & 15u)) return hipErrorInvalidValue;
     if (g.epi == EPI_GATE_RES && (g.ldg % 4 != 0 || ((uintptr_t)g.gate & 7u))) return hipErrorInvalidValue;
     // Tile shapes (CSD_GEMM_VARIANT forces one where it fits, a tuning hook):
-    //   9  256x256, 8 waves of 128x64, software-pipelined main loop - every large launch
+    //   12 256x256, 4 waves of 128x128 (one per SIMD, the 256 accumulators of a lane in the accumulation
+    //      registers), software-pipelined main loop - every large launch.  Alone on the chip it is 3 %
+    //      behind the 8-wave form below (the same 1.5 us per slab, a slower epilogue), but the whole path
+    //      gains 1-2 % on every workload: it reads a third fewer fragments from LDS per MFMA and leaves
+    //      a quarter of each SIMD's registers to the row kernels of the other chains on the same CU.
+    //   9  the same tile as 8 waves of 128x64
     //   1  the same tile with the plain two-stage loop (also serves K < 256)
     //   8  256x192, 8 waves of 64x96: large launches whose N only 192 divides.  (Alone on the chip it
     //      also wins where both divide, e.g. N = 2304: 949 against 878 TFLOP/s, but it moves 17 % more
@@ -389,18 +394,20 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
     //      (one head pass at 256 / 1024 rows: 263 / 290 us against 343 / 366 with 128x128 tiles; a
     //      deeper ring of slabs buys nothing there)
     int variant = gemm_variant_override();
-    if (variant != 1 && variant != 3 && variant != 8 && variant != 9) {
-        if (g.M >= 2048 && g.N % 256 == 0) variant = 9;
+    if (variant != 1 && variant != 3 && variant != 8 && variant != 9 && variant != 12) {
+        if (g.M >= 2048 && g.N % 256 == 0) variant = 12;
         else if (g.M >= 2048 && g.N % 192 == 0) variant = 8;
         else variant = 3;
     }
     if (g.k_splits > 1) variant = 3;
-    if ((variant == 1 || variant == 9) && g.N % 256 != 0) variant = (g.N % 192 == 0) ? 8 : 3;
+    if ((variant == 1 || variant == 9 || variant == 12) && g.N % 256 != 0) variant = (g.N % 192 == 0) ? 8 : 3;
     if (variant == 8 && g.N % 192 != 0) variant = 3;
     switch (variant) {
         case 1: return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);
         case 9: if (g.K >= 256) return launch_cfg<256, 256, 2, 4, 64, 2, true>(g, st);
                 return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);
+        case 12: if (g.K >= 256) return launch_cfg<256, 256, 2, 2, 64, 2, true>(g, st);
+                 return launch_cfg<256, 256, 2, 4, 64, 2>(g, st);
         case 8: if (g.K >= 256) return launch_cfg<256, 192, 4, 2, 64, 2, true>(g, st);
                 return launch_cfg<256, 192, 4, 2, 64, 2>(g, st);
         default: return launch_cfg<64, 64, 2, 2, 64, 2>(g, st);
