@@ -22,6 +22,13 @@
  *     No call synchronises the device except csd_init_head / csd_free_head.
  *   - Every function returning int gives 0 (CSD_OK) or a negative CSD_E* code;
  *     csd_last_error() then holds a message (thread-local).  Nothing aborts.
+ *   - Calls may be enqueued on different streams (default priority) from one host
+ *     thread and then run side by side, each with a workspace of its own: e.g. the
+ *     bonus sample for position gamma+1 beside the target call of a verify window.
+ *     Denoising calls of 8192 rows or more also use the library's own side streams
+ *     of the device; these are shared, so two such calls are correct together but
+ *     share those streams.  Heads are read-only after csd_init_head /
+ *     csd_set_guidance and may serve any number of calls at once.
  *   - Random numbers come from Philox-4x32-10 keyed by `seed` and countered by
  *     the GLOBAL row index row_offset + r, so a workload may be split over
  *     calls (or devices) without changing any result.

@@ -182,3 +182,37 @@ def test_split_phase_bad_calls(B):
         B.csd_denoise_target(dp, dq, torch.zeros((8, 64), device=DEV), 4, 2, 1, 0, 0.0, summ)   # temperature
     B.csd_denoise_draft(dq, torch.zeros((0, 64), device=DEV), 0, 2, 0, 1, 0, 1.0, torch.zeros((0, 81), device=DEV))
     dq.free(); dp.free()
+
+
+def test_bonus_sample_beside_the_target_call_on_a_second_stream(B):
+    """Two calls that need one chain each (no row chunks) may run at the same time on two
+    streams of default priority with their own workspaces: same bits as one after the other."""
+    wl = S.WORKLOADS["mar256"]
+    G, gamma, D = 64, wl.gamma, 16
+    _, _, blobs = H.oracle_heads(wl)
+    dq, dp = H.device_heads(B, wl, blobs)
+    zq, zp = wl.conds(G * gamma)
+    zb = _t(zp[:G])
+    summ_a = torch.zeros((G * gamma, 5 * D + 1), device=DEV)
+    for i in range(gamma):
+        B.csd_denoise_draft(dq, _t(zq.reshape(G, gamma, -1)[:, i]), G, gamma, i, wl.seed, 0, 1.0, summ_a)
+    summ_b = summ_a.clone()
+    B.csd_denoise_target(dp, dq, _t(zp), G, gamma, wl.seed, 0, 1.0, summ_a)
+    bonus_a = B.csd_sample(dp, zb, wl.seed, 0, B.CSD_STREAM_BONUS)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    ws_t = torch.empty(B.csd_workspace_bytes(None, dp, G * gamma), dtype=torch.uint8, device=DEV)
+    ws_b = torch.empty(B.csd_workspace_bytes(dp, None, G), dtype=torch.uint8, device=DEV)
+    bonus_b = torch.empty((G, D), device=DEV)
+    zp_d = _t(zp)
+    for _ in range(3):
+        fork = torch.cuda.Event(); fork.record()
+        side.wait_event(fork)
+        B.csd_sample(dp, zb, wl.seed, 0, B.CSD_STREAM_BONUS, 1.0, tokens=bonus_b, workspace=ws_b, stream=side)
+        join = torch.cuda.Event(); join.record(side)
+        s2 = summ_b.clone()
+        B.csd_denoise_target(dp, dq, zp_d, G, gamma, wl.seed, 0, 1.0, s2, workspace=ws_t)
+        torch.cuda.current_stream().wait_event(join)
+        torch.cuda.synchronize()
+        assert torch.equal(s2, summ_a) and torch.equal(bonus_b, bonus_a)
+    dq.free(); dp.free()
