@@ -25,7 +25,8 @@
  *   - Calls may be enqueued on different streams (default priority) from one host
  *     thread and then run side by side, each with a workspace of its own: e.g. the
  *     bonus sample for position gamma+1 beside the target call of a verify window.
- *     Denoising calls of 8192 rows or more also use the library's own side streams
+ *     Calls that run both heads (csd_denoise_lockstep, csd_denoise_ablation) and
+ *     single-head calls of 8192 rows or more also use the library's own side streams
  *     of the device; these are shared, so two such calls are correct together but
  *     share those streams.  Heads are read-only after csd_init_head /
  *     csd_set_guidance and may serve any number of calls at once.
