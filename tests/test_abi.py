@@ -77,3 +77,12 @@ def test_argument_errors_without_device_work(B):
     assert lib.csd_denoise_ablation(None, None, None, None, 1, 1, 0, 0, 1.0, 0, None, None, None, 0, None) == B.CSD_EINVAL
     assert b"NULL head" in lib.csd_last_error()
     lib.csd_free_head(None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path has no cross-GPU step and every box has one GPU: bench.py says so and exits."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
