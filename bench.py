@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--ddim-eta", type=float, default=None, help="use the DDIM sampler with this eta (default: DDPM)")
     ap.add_argument("--cfg-scale", type=float, default=None,
                     help="classifier-free guidance with this scale in both heads (two conditioning vectors per row)")
+    ap.add_argument("--temperature", type=float, default=1.0, help="sampler temperature tau (scales sigma_t in both heads)")
     ap.add_argument("--ratio-mode", default=None, choices=[None, "aligned", "unaligned", "single_path"],
                     help="form the path ratio as in the paper's comparison of calculation approaches "
                          "(csd_denoise_ablation) instead of the method's lockstep call")
@@ -106,13 +107,15 @@ def main():
     summary = torch.empty((R, 5 * D + 1), dtype=torch.float32, device=dev)
     dist2 = torch.empty((R,), dtype=torch.float32, device=dev)
 
+    tau = a.temperature
+
     def step():
         if ratio_mode is None:
-            B.csd_denoise_lockstep(h_q, h_p, z_q, z_p, G, gamma, wl.seed, 0, 1.0, summary, ws)
+            B.csd_denoise_lockstep(h_q, h_p, z_q, z_p, G, gamma, wl.seed, 0, tau, summary, ws)
         else:
-            B.csd_denoise_ablation(h_q, h_p, z_q, z_p, G, gamma, wl.seed, 0, 1.0, ratio_mode, summary, dist2, ws)
-        n_acc, ell, mask = B.csd_verify(summary, G, gamma, D, wl.seed)
-        out = B.csd_resample(summary, n_acc, G, gamma, D, wl.seed)
+            B.csd_denoise_ablation(h_q, h_p, z_q, z_p, G, gamma, wl.seed, 0, tau, ratio_mode, summary, dist2, ws)
+        n_acc, ell, mask = B.csd_verify(summary, G, gamma, D, wl.seed, 0, tau)
+        out = B.csd_resample(summary, n_acc, G, gamma, D, wl.seed, 0, tau)
         return n_acc, ell, mask, out
 
     for _ in range(a.warmup):
@@ -184,7 +187,7 @@ def main():
             wl.n_steps, R, G, gamma), "rows_per_step": R, "gamma": gamma, "out_scale": wl.out_scale,
             "eps_skip_gain": wl.eps_skip_gain,
             "sampler": "ddpm" if a.ddim_eta is None else "ddim(eta=%g)" % a.ddim_eta,
-            "cfg_scale": a.cfg_scale, "ratio_mode": a.ratio_mode},
+            "cfg_scale": a.cfg_scale, "ratio_mode": a.ratio_mode, "temperature": tau},
         "wall_s": wall,
         "whole_path": {"algorithmic_TFLOP_per_s": flops_row * R * a.steps / (ms / 1e3) / 1e12,
                        "frac_of_peak": flops_row * R * a.steps / (ms / 1e3) / 1e12 / peak,
@@ -281,11 +284,11 @@ def main():
         t_init = time.perf_counter() - t0
         t0 = time.perf_counter()
         if ratio_mode is None:
-            s_o, _ = O.denoise_lockstep(o_q, o_p, zq_h[:n], zp_h[:n], wl.seed)
+            s_o, _ = O.denoise_lockstep(o_q, o_p, zq_h[:n], zp_h[:n], wl.seed, 0, tau)
         else:
-            s_o, _ = O.denoise_ablation(o_q, o_p, zq_h[:n], zp_h[:n], wl.seed, 0, 1.0, ratio_mode)
-        n_o, ell_o, mask_o, log_u = O.verify(s_o, n // gamma, gamma, wl.seed)
-        O.resample(s_o, n_o, n // gamma, gamma, wl.seed)
+            s_o, _ = O.denoise_ablation(o_q, o_p, zq_h[:n], zp_h[:n], wl.seed, 0, tau, ratio_mode)
+        n_o, ell_o, mask_o, log_u = O.verify(s_o, n // gamma, gamma, wl.seed, 0, tau)
+        O.resample(s_o, n_o, n // gamma, gamma, wl.seed, 0, tau)
         dt = time.perf_counter() - t0
         x_g, x_o = summary[:n].cpu().numpy()[:, 4 * D:5 * D], s_o[:, 4 * D:5 * D]
         clear = np.abs(log_u - ell_o) >= 1e-3
