@@ -149,3 +149,31 @@ def test_ablation_bad_calls(B):
     s, d = B.csd_denoise_ablation(dq, dp, torch.zeros((0, 64), device=DEV), torch.zeros((0, 64), device=DEV), 0, 2, 1, 0, 1.0, 1)
     assert s.shape[0] == 0 and d.numel() == 0
     dq.free(); dp.free()
+
+
+@pytest.mark.parametrize("mode", [O.RATIO_UNALIGNED, O.RATIO_SINGLE_PATH])
+def test_ratio_modes_with_guidance_and_ddim_f32(B, mode):
+    """The comparison modes on heads that use the DDIM sampler and classifier-free guidance (two
+    head rows per trajectory row; the stored path and the own final sample have one row each)."""
+    wl = S.WORKLOADS["tiny"].with_(gamma=2, out_scale=0.02)
+    G, gamma, D, off, seed, tau, scale, eta = 45, 2, 16, 64, wl.seed, 0.9, 1.5, 0.7
+    R = G * gamma
+    tb, db, ds = wl.heads(0.05)
+    ocfg = lambda: O.HeadCfg(16, 64, 128, 2, wl.n_steps, eps_skip_gain=wl.eps_skip_gain, cfg_scale=scale,
+                             sampler="ddim", ddim_eta=eta)
+    oq, op = O.Head(ocfg(), db), O.Head(ocfg(), tb)
+    dq, dp = H.device_heads(B, wl, (db, ds, tb), "f32", ddim_eta=eta)
+    B.csd_set_guidance(dq, True, scale); B.csd_set_guidance(dp, True, scale)
+    zq, zp = wl.conds(128)
+    uq, up = wl.conds(128, 64 * 2000)
+    zq2 = np.stack([zq, uq], 1).astype(np.float32)[:R]
+    zp2 = np.stack([zp, up], 1).astype(np.float32)[:R]
+    want, dist_o = O.denoise_ablation(oq, op, zq2, zp2, seed, off, tau, mode)
+    got, dist_g = B.csd_denoise_ablation(dq, dp, _t(zq2), _t(zp2), G, gamma, seed, off, tau, mode)
+    got, dist_g = got.cpu().numpy(), dist_g.cpu().numpy()
+    assert H.rel_err(got[:, 4 * D:5 * D], want[:, 4 * D:5 * D]) < H.F32_TOL
+    assert H.rel_err(got[:, 0:D], want[:, 0:D]) < H.F32_TOL
+    lr = want[:, -1]
+    assert np.max(np.abs(got[:, -1] - lr)) < H.F32_TOL * 10 * max(1.0, np.abs(lr).max())
+    assert np.all(np.abs(dist_g - dist_o) <= _dist_tol(dist_o, want[:, 4 * D:5 * D], H.F32_TOL, D) + 1e-12)
+    dq.free(); dp.free()
