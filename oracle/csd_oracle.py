@@ -48,6 +48,7 @@ STREAM_RESAMPLE_N = 2  # slot k: proposal noise of resampling trial k
 STREAM_RESAMPLE_U = 3  # slot k: uniform of resampling trial k
 STREAM_BONUS = 4     # trajectory noise of the target-only sample x ~ p_{gamma+1}, keyed by the global GROUP index
 STREAM_TRAJ_P = 5    # the target's own trajectory noise when the two paths are NOT aligned (ablation), slots as stream 0
+STREAM_GMM_PICK = 6  # mixture heads: the uniform that picks a component; slot 0: the draft's sample, slot 1+k: resampling trial k
 
 # how the path ratio before the final step is formed (Table 1 of the paper)
 RATIO_ALIGNED = 0      # p(Y_p)/q(Y_q), eps^p_t = eps^q_t: the method
@@ -698,4 +699,125 @@ def resample(summary, n_accept, n_groups: int, gamma: int, seed: int,
             records[g].append((float(a_s[i]), float(uk[i])))
         pending = pending[~(uk <= a_s)]
     flags[pending] |= FLAG_CAP                          # never accepted within max_trips
+    return tokens, n_out, trips, flags, records
+
+
+# --------------------------------------------------------------------------
+# Mixture-of-Gaussians output heads (the appendix on other forms of the output
+# distribution): p(x) = sum_k pi_k N(x; mu_k, Sigma_k), diagonal Sigma_k.  The
+# densities are explicit, so the accept test uses p(x)/q(x) itself and the
+# modified distribution max(0, p - q)/Z is sampled by acceptance-rejection with
+# proposal p and threshold max(0, p(x) - q(x))/p(x).
+# A mixture is (pi [R,K] >= 0, not necessarily summing to 1; mu [R,K,D]; logvar [R,K,D]).
+# --------------------------------------------------------------------------
+def gmm_logpdf(x, pi, mu, logvar):
+    """log sum_k (pi_k / sum pi) N(x; mu_k, diag exp(logvar_k)) per row, by log-sum-exp."""
+    x = np.asarray(x, dtype=np.float64); pi = np.asarray(pi, dtype=np.float64)
+    mu = np.asarray(mu, dtype=np.float64); logvar = np.asarray(logvar, dtype=np.float64)
+    comp = -0.5 * np.sum((x[:, None, :] - mu) ** 2 / np.exp(logvar) + logvar + LOG_2PI, axis=-1)   # [R,K]
+    with np.errstate(divide="ignore"):
+        a = comp + np.log(pi) - np.log(np.sum(pi, axis=1, keepdims=True))
+    m = np.max(a, axis=1, keepdims=True)
+    return (m + np.log(np.sum(np.exp(a - m), axis=1, keepdims=True)))[:, 0]
+
+
+def gmm_pick(pi, u):
+    """Component of each row for the uniform u: the first k whose running sum of pi reaches
+    u * sum(pi).  The sums are taken in fp32, left to right, and compared in fp32, so that
+    a device doing the same additions picks the same component."""
+    pi32 = np.asarray(pi, dtype=np.float32)
+    R, K = pi32.shape
+    total = np.zeros(R, dtype=np.float32)
+    for k in range(K):
+        total = total + pi32[:, k]
+    thr = np.asarray(u, dtype=np.float32) * total
+    run = np.zeros(R, dtype=np.float32)
+    pick = np.full(R, K - 1, dtype=np.int64)
+    done = np.zeros(R, dtype=bool)
+    for k in range(K):
+        run = run + pi32[:, k]
+        hit = (~done) & (run >= thr)
+        pick[hit] = k
+        done |= hit
+    return pick
+
+
+def gmm_sample(pi, mu, logvar, u, eps):
+    """x = mu_k + sigma_k eps with k = gmm_pick(pi, u)."""
+    k = gmm_pick(pi, u)
+    r = np.arange(k.shape[0])
+    mu = np.asarray(mu, dtype=np.float64); logvar = np.asarray(logvar, dtype=np.float64)
+    return mu[r, k] + np.exp(0.5 * logvar[r, k]) * eps, k
+
+
+def gmm_draft_sample(pi_q, mu_q, logvar_q, seed: int, row_offset: int = 0):
+    """The draft tokens x_i ~ q_i: component from STREAM_GMM_PICK slot 0, noise from
+    STREAM_TRAJ slot 0 (the counters of the row's final reverse step in the diffusion form)."""
+    R, K, D = np.asarray(mu_q).shape
+    rows = row_offset + np.arange(R, dtype=np.uint64)
+    x, _ = gmm_sample(pi_q, mu_q, logvar_q, uniforms(seed, rows, 0, STREAM_GMM_PICK),
+                      normals(seed, rows, 0, STREAM_TRAJ, D))
+    return x
+
+
+def gmm_verify(x, pi_p, mu_p, logvar_p, pi_q, mu_q, logvar_q, n_groups: int, gamma: int, seed: int,
+               row_offset: int = 0):
+    """Accept test r_i <= p_i(x_i)/q_i(x_i) and first-reject scan (Alg. 1 with explicit densities).
+    Returns (n_accept [G], log_ratio [R], mask [R], log_u [R])."""
+    R = n_groups * gamma
+    ell = gmm_logpdf(x, pi_p, mu_p, logvar_p) - gmm_logpdf(x, pi_q, mu_q, logvar_q)
+    ell = np.where(np.isfinite(ell), ell, -np.inf)
+    rows = row_offset + np.arange(R, dtype=np.uint64)
+    log_u = np.log(uniforms(seed, rows, 0, STREAM_ACCEPT_U))
+    mask = log_u <= ell
+    n_acc = np.full(n_groups, gamma, dtype=np.int32)
+    for g in range(n_groups):
+        for i in range(gamma):
+            if not mask[g * gamma + i]:
+                n_acc[g] = i
+                break
+    return n_acc, ell, mask.astype(np.uint8), log_u
+
+
+def gmm_resample(x, n_accept, pi_p, mu_p, logvar_p, pi_q, mu_q, logvar_q, n_groups: int, gamma: int,
+                 seed: int, row_offset: int = 0, max_trips: int = 1024):
+    """At the first rejected row of each group: propose x' ~ p (component from STREAM_GMM_PICK
+    slot 1+k, noise from STREAM_RESAMPLE_N slot k) and keep it when the uniform of
+    STREAM_RESAMPLE_U slot k is <= alpha_s = max(0, p(x') - q(x'))/p(x').  Emits as resample():
+    tokens [G, gamma+1, D], n_out, trips, flags, per-group (alpha_s, u) records."""
+    x = np.asarray(x, dtype=np.float64)
+    D = x.shape[1]
+    n_accept = np.asarray(n_accept, dtype=np.int64)
+    pi_p = np.asarray(pi_p); mu_p = np.asarray(mu_p); logvar_p = np.asarray(logvar_p)
+    pi_q = np.asarray(pi_q); mu_q = np.asarray(mu_q); logvar_q = np.asarray(logvar_q)
+    tokens = np.zeros((n_groups, gamma + 1, D))
+    n_out = np.full(n_groups, gamma, dtype=np.int32)
+    trips = np.zeros(n_groups, dtype=np.int32)
+    flags = np.zeros(n_groups, dtype=np.uint32)
+    records = [None] * n_groups
+    for g in range(n_groups):
+        tokens[g, :int(n_accept[g])] = x[g * gamma: g * gamma + int(n_accept[g])]
+    pending = np.nonzero(n_accept < gamma)[0]
+    for g in pending:
+        records[g] = []
+    n_out[pending] = n_accept[pending] + 1
+    for k in range(max_trips):
+        if pending.size == 0:
+            break
+        j = pending * gamma + n_accept[pending]
+        rows = (row_offset + j).astype(np.uint64)
+        xp, _ = gmm_sample(pi_p[j], mu_p[j], logvar_p[j], uniforms(seed, rows, 1 + k, STREAM_GMM_PICK),
+                           normals(seed, rows, k, STREAM_RESAMPLE_N, D))
+        a = gmm_logpdf(xp, pi_q[j], mu_q[j], logvar_q[j]) - gmm_logpdf(xp, pi_p[j], mu_p[j], logvar_p[j])
+        bad = np.isnan(a)
+        a_s = np.where(a < 0.0, -np.expm1(np.minimum(a, 0.0)), 0.0)
+        a_s = np.where(bad, 0.0, a_s)
+        flags[pending[bad]] |= FLAG_NONFINITE
+        uk = uniforms(seed, rows, k, STREAM_RESAMPLE_U)
+        tokens[pending, n_accept[pending]] = xp
+        trips[pending] = k + 1
+        for i, g in enumerate(pending):
+            records[g].append((float(a_s[i]), float(uk[i])))
+        pending = pending[~(uk <= a_s)]
+    flags[pending] |= FLAG_CAP
     return tokens, n_out, trips, flags, records

@@ -767,3 +767,103 @@ def test_structure_of_the_ratio_comparison_on_synthetic_heads():
         assert dist[O.RATIO_ALIGNED] < 0.05 * dist[O.RATIO_UNALIGNED]
         kl.append(-lr[O.RATIO_SINGLE_PATH].mean())
     assert 0 < kl[0] < kl[1]
+
+
+# -------------------------------------------- mixture-of-Gaussians heads ----
+def _mix_1d(G, comps, D=4):
+    """G identical rows of a mixture that varies in coordinate 0 only: comps = [(weight, mean, sd)];
+    the other coordinates are N(0,1) in every component, so they factor out of any density ratio."""
+    K = len(comps)
+    pi = np.tile(np.array([c[0] for c in comps], dtype=np.float32), (G, 1))
+    mu = np.zeros((G, K, D), dtype=np.float32); lv = np.zeros((G, K, D), dtype=np.float32)
+    for k, (_, m, sd) in enumerate(comps):
+        mu[:, k, 0] = m; lv[:, k, 0] = 2 * math.log(sd)
+    return pi, mu, lv
+
+
+def _mix_pdf(comps):
+    tot = sum(c[0] for c in comps)
+    return lambda x: sum(w / tot * stats.norm.pdf(x, m, sd) for w, m, sd in comps)
+
+
+def _mix_cdf(comps):
+    tot = sum(c[0] for c in comps)
+    return lambda x: sum(w / tot * stats.norm.cdf(x, m, sd) for w, m, sd in comps)
+
+
+def test_gmm_logpdf_against_scipy():
+    rng = np.random.default_rng(4)
+    R, K, D = 9, 3, 4
+    pi = rng.uniform(0.1, 2.0, size=(R, K)); mu = rng.normal(size=(R, K, D)); lv = rng.normal(scale=0.5, size=(R, K, D))
+    x = rng.normal(size=(R, D))
+    want = np.array([math.log(sum(pi[r, k] / pi[r].sum() * stats.multivariate_normal.pdf(x[r], mu[r, k], np.diag(np.exp(lv[r, k])))
+                                  for k in range(K))) for r in range(R)])
+    assert np.allclose(O.gmm_logpdf(x, pi, mu, lv), want, rtol=1e-12, atol=1e-12)
+    # far in the tail the log-sum-exp still returns the dominant component's log-density
+    far = O.gmm_logpdf(x + 60.0, pi, mu, lv)
+    assert np.all(np.isfinite(far)) and np.all(far < -500)
+
+
+def test_gmm_pick_and_sampler_distribution():
+    comps = [(0.4, -1.5, 0.5), (1.0, 0.2, 0.8), (0.0, 9.0, 1.0), (0.6, 2.5, 0.3)]      # weights need not sum to 1
+    G = 80000
+    pi, mu, lv = _mix_1d(G, comps)
+    rows = np.arange(G, dtype=np.uint64)
+    u = O.uniforms(3, rows, 0, O.STREAM_GMM_PICK)
+    k = O.gmm_pick(pi, u)
+    freq = np.bincount(k, minlength=4) / G
+    assert freq[2] == 0.0                                                           # a zero-weight component is never drawn
+    assert np.allclose(freq, [0.2, 0.5, 0.0, 0.3], atol=4 * math.sqrt(0.25 / G))
+    assert np.array_equal(O.gmm_pick(pi[:2], np.array([1e-7, 1 - 1e-7])), [0, 3])
+    x = O.gmm_draft_sample(pi, mu, lv, 3)
+    assert stats.kstest(x[:, 0], _mix_cdf(comps)).pvalue > 1e-3
+    assert stats.kstest(x[:, 2], "norm").pvalue > 1e-3
+
+
+def test_gmm_accept_resample_is_lossless():
+    """With explicit densities the scheme is the discrete one in continuous form: P(accept) =
+    1 - TV(p, q), resampled tokens follow max(0, p - q)/Z, and accepted-or-resampled tokens
+    follow p exactly (the appendix on other forms of the output distribution)."""
+    G, seed = 60000, 17
+    pc = [(0.5, -1.0, 0.6), (0.5, 1.2, 0.5)]
+    qc = [(0.7, -0.6, 0.9), (0.3, 1.6, 0.7)]
+    pp, mp, lp = _mix_1d(G, pc); pq, mq, lq = _mix_1d(G, qc)
+    x = O.gmm_draft_sample(pq, mq, lq, seed)
+    n_acc, ell, mask, _ = O.gmm_verify(x, pp, mp, lp, pq, mq, lq, G, 1, seed)
+    p, q = _mix_pdf(pc), _mix_pdf(qc)
+    assert np.allclose(ell, np.log(p(x[:, 0])) - np.log(q(x[:, 0])), atol=1e-4)      # (the fp32 inputs hold 2 log sd rounded)
+    tv, _ = integrate.quad(lambda t: max(0.0, p(t) - q(t)), -12, 12, limit=800)
+    assert mask.mean() == pytest.approx(1 - tv, abs=4 * math.sqrt(tv * (1 - tv) / G))
+    tok, n_out, trips, flags, _ = O.gmm_resample(x, n_acc, pp, mp, lp, pq, mq, lq, G, 1, seed)
+    assert np.all(flags == 0) and np.all(n_out == 1)
+    rej = n_acc == 0
+    xs = np.linspace(-12, 12, 24001)
+    res_cdf = np.cumsum(np.maximum(0, p(xs) - q(xs))) * (xs[1] - xs[0]) / tv
+    assert stats.kstest(tok[rej, 0, 0], lambda t: np.interp(t, xs, res_cdf)).pvalue > 1e-3
+    assert stats.kstest(tok[:, 0, 0], _mix_cdf(pc)).pvalue > 1e-3
+    assert trips[rej].mean() == pytest.approx(1 / tv, rel=0.03) and np.all(trips[~rej] == 0)
+    # identical mixtures: ratio 1, everything accepted
+    n_acc, ell, mask, _ = O.gmm_verify(x, pq, mq, lq, pq, mq, lq, G, 1, seed)
+    assert np.all(ell == 0.0) and np.all(mask == 1)
+
+
+def test_gmm_with_one_component_is_the_gaussian_case():
+    """K = 1 is the final-step Gaussian of the diffusion form with Sigma = 1: same log-ratio,
+    same decisions, same resampled tokens as verify() / resample() on the equivalent summary."""
+    G, gamma, seed, off = 300, 2, 9, 128
+    R = G * gamma
+    rng = np.random.default_rng(0)
+    mp = rng.normal(size=(R, 4)).astype(np.float32); mq = (mp + 0.4 * rng.normal(size=(R, 4))).astype(np.float32)
+    lp = rng.normal(scale=0.3, size=(R, 4)).astype(np.float32); lq = rng.normal(scale=0.3, size=(R, 4)).astype(np.float32)
+    one = np.ones((R, 1), dtype=np.float32)
+    x = O.gmm_draft_sample(one, mq[:, None], lq[:, None], seed, off)
+    rows = off + np.arange(R, dtype=np.uint64)
+    assert np.allclose(x, mq + np.exp(0.5 * lq.astype(np.float64)) * O.normals(seed, rows, 0, O.STREAM_TRAJ, 4))
+    summ = np.concatenate([mp, lp, mq, lq, x, np.zeros((R, 1))], axis=1)
+    n1, e1, m1, _ = O.verify(summ, G, gamma, seed, off)
+    n2, e2, m2, _ = O.gmm_verify(x, one, mp[:, None], lp[:, None], one, mq[:, None], lq[:, None], G, gamma, seed, off)
+    assert np.allclose(e1, e2, atol=1e-10) and np.array_equal(m1, m2) and np.array_equal(n1, n2)
+    t1, o1, k1, f1, _ = O.resample(summ, n1, G, gamma, seed, off)
+    t2, o2, k2, f2, _ = O.gmm_resample(x, n2, one, mp[:, None], lp[:, None], one, mq[:, None], lq[:, None], G, gamma, seed, off)
+    assert np.allclose(t1, t2) and np.array_equal(o1, o2) and np.array_equal(k1, k2) and np.array_equal(f1, f2)
+    assert (n1 < gamma).sum() > 50
