@@ -44,6 +44,68 @@ def measured_traffic(workload, dtype, rows):
     return vals["traffic_bytes_per_launch"]
 
 
+def gmm_bench(a, np, torch, B, S):
+    """Mixture-of-Gaussians heads (the appendix on other forms of the output distribution): the whole
+    path is three row kernels over the mixture parameters, bound by HBM.  One JSON line."""
+    K, D, gamma, seed, dev = a.gmm_components, 16, 4, 1234, "cuda:0"
+    R = (a.rows or (1 << 20)) // gamma * gamma
+    G = R // gamma
+    base_p, base_q = S.mixture_pair(4096, K, D, seed)           # tiled: 4096 distinct rows
+    rep = (R + 4095) // 4096
+    tile = lambda m: tuple(torch.from_numpy(t).to(dev).repeat((rep,) + (1,) * (t.ndim - 1))[:R].contiguous() for t in m)
+    mp, mq = tile(base_p), tile(base_q)
+
+    def step():
+        x = B.csd_gmm_draft_sample(mq, seed)
+        n, ell, mask = B.csd_gmm_verify(x, mp, mq, G, gamma, seed)
+        return x, n, mask, B.csd_gmm_resample(x, n, mp, mq, G, gamma, seed)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(a.steps):
+        x, n, mask, (tok, n_out, trips, flags) = step()
+    e1.record(); torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1)
+    # the accept test alone (the dominant kernel: it reads both mixtures of every row once)
+    v0, v1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    v0.record()
+    for _ in range(a.steps):
+        B.csd_gmm_verify(x, mp, mq, G, gamma, seed)
+    v1.record(); torch.cuda.synchronize()
+    v_ms = v0.elapsed_time(v1) / a.steps
+    alg = R * (2 * K * (1 + 2 * D) + D) * 4 + R * 5 + G * 4       # both mixtures + x in; log-ratio, mask, n out
+    res = {"metric": "verified tokens/sec (mixture heads: draft sample + accept test + resample)",
+           "value": R * a.steps / (ms / 1e3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+           "ms_per_step": ms / a.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": "mixture heads: K=%d components, D=%d, rows/step=%d (gamma=%d)" % (K, D, R, gamma)},
+           "acceptance": {"row_accept_rate": float(mask.float().mean()), "resample_trips_mean":
+                          float(trips[trips > 0].float().mean()) if bool((trips > 0).any()) else 0.0,
+                          "resample_trips_max": int(trips.max()), "cap_flags": int((flags & 1).sum())},
+           "roofline": {"bound": "hbm", "kernel": "accept test over both mixtures", "achieved": alg / (v_ms / 1e3) / 1e9,
+                        "peak": 8000.0, "unit": "GB/s", "frac": alg / (v_ms / 1e3) / 1e9 / 8000.0,
+                        "avg_launch_ms": v_ms, "algorithmic_bytes_per_launch": alg, "traffic": None}}
+    if a.oracle_rows > 0:
+        from oracle import csd_oracle as O
+        nr = min(a.oracle_rows * 64 // gamma * gamma, 4096, R)
+        sl = lambda m: tuple(t[:nr] for t in m)
+        t0 = time.perf_counter()
+        xo = O.gmm_draft_sample(*sl(base_q), seed)
+        n_o, ell_o, mask_o, log_u = O.gmm_verify(xo, *sl(base_p), *sl(base_q), nr // gamma, gamma, seed)
+        O.gmm_resample(xo, n_o, *sl(base_p), *sl(base_q), nr // gamma, gamma, seed)
+        dt = time.perf_counter() - t0
+        clear = np.abs(log_u - ell_o) >= 1e-3
+        res["cpu_baseline"] = {"value": nr / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                               "sample": "first %d rows, fp64 numpy oracle, %.1f s" % (nr, dt)}
+        res["parity_on_sample"] = {"rows": nr, "token_max_abs_err": float(np.max(np.abs(x[:nr].cpu().numpy() - xo))),
+                                   "decision_agreement_outside_band":
+                                       float((mask[:nr].cpu().numpy().astype(bool) == (log_u <= ell_o))[clear].mean())}
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -60,6 +122,9 @@ def main():
     ap.add_argument("--ratio-mode", default=None, choices=[None, "aligned", "unaligned", "single_path"],
                     help="form the path ratio as in the paper's comparison of calculation approaches "
                          "(csd_denoise_ablation) instead of the method's lockstep call")
+    ap.add_argument("--gmm-components", type=int, default=0,
+                    help="measure the mixture-of-Gaussians head path instead (draft sample + accept test + resampling "
+                         "with this many components per mixture; --rows rows, default 2^20)")
     ap.add_argument("--no-latency-shape", action="store_true", help="skip the split-phase latency-shape figure")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="after the timed steps, copy 256 MiB device to device once (a kernel of known "
@@ -74,6 +139,8 @@ def main():
     from paper_2411_11925_amd import binding as B
     from paper_2411_11925_amd import synth as S
 
+    if a.gmm_components > 0:
+        return gmm_bench(a, np, torch, B, S)
     wl = S.WORKLOADS[a.workload]
     dtype = a.dtype or wl.gemm_dtype
     wl = wl.with_(gemm_dtype=dtype)

@@ -77,6 +77,8 @@ extern "C" {
                                     its "row" is the global GROUP index */
 #define CSD_STREAM_TRAJ_P      5  /* the target's own x_T and eps_t when the two paths are not aligned
                                     (csd_denoise_ablation, CSD_RATIO_UNALIGNED); slots as in stream 0 */
+#define CSD_STREAM_GMM_PICK    6  /* mixture heads: the uniform that picks a component; slot 0: the draft's
+                                    sample, slot 1+k: resampling trial k */
 
 /* how csd_denoise_ablation forms the path ratio before the final step (Table 1) */
 #define CSD_RATIO_ALIGNED      0  /* p(Y_p)/q(Y_q) with eps^p_t = eps^q_t (Sec. 3.2): the method */
@@ -297,6 +299,40 @@ int csd_resample(const float* summary, const int32_t* n_accept,
  */
 int csd_append_bonus(float* tokens, int32_t* n_out, const int32_t* n_accept, const float* bonus,
                      int64_t n_groups, int32_t gamma, int32_t token_dim, void* hip_stream);
+
+/*
+ * Mixture-of-Gaussians output heads (the appendix on other forms of the output
+ * distribution): the models emit, per row, p(x) = sum_k pi_k N(x; mu_k, Sigma_k) with
+ * diagonal Sigma_k instead of running a diffusion head.  With explicit densities the accept
+ * test of Alg. 1 is r <= p(x)/q(x), and the modified distribution max(0, p - q)/Z is
+ * sampled by acceptance-rejection with proposal p and threshold max(0, p(x') - q(x'))/p(x').
+ * A mixture is three device arrays, fp32: pi [R, K] (>= 0, need not sum to 1; a component
+ * with pi = 0 is never drawn), mu [R, K, D], logvar [R, K, D].  1 <= K <= 64, D in {4, 8, 16}.
+ *
+ * csd_gmm_draft_sample: x [R, D] (device, written) = the draft tokens x_i ~ q_i; the
+ *   component comes from stream CSD_STREAM_GMM_PICK slot 0 (first k whose running fp32 sum
+ *   of pi reaches u * sum pi), the noise from stream CSD_STREAM_TRAJ slot 0.
+ * csd_gmm_verify: as csd_verify with log_ratio = log p(x) - log q(x); outputs as there.
+ * csd_gmm_resample: as csd_resample; trial k draws its component from stream
+ *   CSD_STREAM_GMM_PICK slot 1+k, its noise from CSD_STREAM_RESAMPLE_N slot k and its
+ *   uniform from CSD_STREAM_RESAMPLE_U slot k; x is the array of draft tokens that
+ *   csd_gmm_verify judged.  tokens [G, gamma+1, D], n_out, trips, flags as in csd_resample.
+ * n_rows / n_groups = 0 is a no-op.  Errors: CSD_EINVAL, CSD_EHIP.
+ */
+int csd_gmm_draft_sample(const float* pi_q, const float* mu_q, const float* logvar_q, int64_t n_rows,
+                         int32_t n_components, int32_t token_dim, uint64_t seed, uint64_t row_offset,
+                         float* x, void* hip_stream);
+int csd_gmm_verify(const float* x, const float* pi_p, const float* mu_p, const float* logvar_p,
+                   const float* pi_q, const float* mu_q, const float* logvar_q, int64_t n_groups,
+                   int32_t gamma, int32_t n_components, int32_t token_dim, uint64_t seed,
+                   uint64_t row_offset, int32_t* n_accept, float* log_ratio, uint8_t* accept_mask,
+                   void* hip_stream);
+int csd_gmm_resample(const float* x, const int32_t* n_accept, const float* pi_p, const float* mu_p,
+                     const float* logvar_p, const float* pi_q, const float* mu_q, const float* logvar_q,
+                     int64_t n_groups, int32_t gamma, int32_t n_components, int32_t token_dim,
+                     uint64_t seed, uint64_t row_offset, int32_t max_trips, float* tokens,
+                     int32_t* n_out, int32_t* trips, uint32_t* flags, void* hip_stream);
+
 
 /*
  * Stage-wise access for tests and profiling: one head evaluation

@@ -18,7 +18,10 @@ What it computes, in the paper's order and notation (numpy, float64):
   * the accept test of Alg. 1 with ratio Sigma * p(x0|x1^p) / q(x0|x1^q)
     (Eq. 7) and the first-reject scan,
   * acceptance-rejection resampling from max(0, p - q)/Z with the threshold of
-    Corollary 1 (Eq. 8-10; Alg. 1 repeat-until loop), proposal p(.|x1^p).
+    Corollary 1 (Eq. 8-10; Alg. 1 repeat-until loop), proposal p(.|x1^p),
+  * the same accept test and resampling for mixture-of-Gaussians output heads
+    (the appendix on other forms of the output distribution), where p(x) and
+    q(x) are explicit.
 
 The diffusion head itself is not defined by the paper ("a neural network with
 parameter theta", Sec. 3.1); the adaLN residual MLP used here is this build's

@@ -28,13 +28,14 @@ CSD_COSINE, CSD_TABLE = 0, 1
 CSD_STREAM_TRAJ, CSD_STREAM_ACCEPT_U, CSD_STREAM_RESAMPLE_N, CSD_STREAM_RESAMPLE_U = 0, 1, 2, 3
 CSD_STREAM_BONUS = 4
 CSD_STREAM_TRAJ_P = 5
+CSD_STREAM_GMM_PICK = 6
 CSD_RATIO_ALIGNED, CSD_RATIO_UNALIGNED, CSD_RATIO_SINGLE_PATH = 0, 1, 2
 CSD_SAMPLER_DDPM, CSD_SAMPLER_DDIM = 0, 1
 CSD_FLAG_CAP, CSD_FLAG_NONFINITE = 1, 2
 
 EXPORTS = ["csd_param_count", "csd_init_head", "csd_free_head", "csd_set_guidance", "csd_workspace_bytes",
            "csd_denoise_lockstep", "csd_ablation_workspace_bytes", "csd_denoise_ablation", "csd_denoise_draft", "csd_denoise_target", "csd_sample",
-           "csd_verify", "csd_resample", "csd_append_bonus", "csd_head_eval",
+           "csd_verify", "csd_resample", "csd_append_bonus", "csd_gmm_draft_sample", "csd_gmm_verify", "csd_gmm_resample", "csd_head_eval",
            "csd_rng_normals", "csd_rng_uniforms", "csd_gemm_bf16", "csd_profile_enable", "csd_profile_read", "csd_last_error"]
 
 
@@ -83,6 +84,14 @@ _lib.csd_verify.argtypes = [c_void_p, c_int64, c_int32, c_int32, c_uint64, c_uin
 _lib.csd_resample.restype = c_int
 _lib.csd_resample.argtypes = [c_void_p, c_void_p, c_int64, c_int32, c_int32, c_uint64, c_uint64, c_float,
                               c_int32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+_lib.csd_gmm_draft_sample.restype = c_int
+_lib.csd_gmm_draft_sample.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int32, c_int32, c_uint64, c_uint64, c_void_p, c_void_p]
+_lib.csd_gmm_verify.restype = c_int
+_lib.csd_gmm_verify.argtypes = [c_void_p] * 7 + [c_int64, c_int32, c_int32, c_int32, c_uint64, c_uint64, c_void_p, c_void_p,
+                                                 c_void_p, c_void_p]
+_lib.csd_gmm_resample.restype = c_int
+_lib.csd_gmm_resample.argtypes = [c_void_p] * 8 + [c_int64, c_int32, c_int32, c_int32, c_uint64, c_uint64, c_int32, c_void_p,
+                                                   c_void_p, c_void_p, c_void_p, c_void_p]
 _lib.csd_head_eval.restype = c_int
 _lib.csd_head_eval.argtypes = [c_void_p, c_void_p, c_void_p, c_int32, c_int64, c_void_p, c_void_p,
                                c_size_t, c_void_p]
@@ -323,6 +332,58 @@ def csd_resample(summary: torch.Tensor, n_accept: torch.Tensor, n_groups: int, g
     _check(_lib.csd_resample(_ptr(summary), _ptr(n_accept), n_groups, gamma, token_dim, seed, row_offset,
                              temperature, max_trips, _ptr(tokens), _ptr(n_out), _ptr(trips), _ptr(flags),
                              _stream(stream)))
+    return tokens, n_out, trips, flags
+
+
+def _mix(m, R):
+    """(pi [R,K], mu [R,K,D], logvar [R,K,D]) -> checked, with K and D."""
+    pi, mu, lv = m
+    K, D = mu.shape[1], mu.shape[2]
+    for t, shape in ((pi, (R, K)), (mu, (R, K, D)), (lv, (R, K, D))):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == shape
+    return K, D
+
+
+def csd_gmm_draft_sample(mix_q, seed: int, row_offset: int = 0, stream=None) -> torch.Tensor:
+    R = mix_q[0].shape[0]
+    K, D = _mix(mix_q, R)
+    x = torch.empty((R, D), dtype=torch.float32, device=mix_q[0].device)
+    _check(_lib.csd_gmm_draft_sample(_ptr(mix_q[0]), _ptr(mix_q[1]), _ptr(mix_q[2]), R, K, D, seed, row_offset, _ptr(x),
+                                     _stream(stream)))
+    return x
+
+
+def csd_gmm_verify(x: torch.Tensor, mix_p, mix_q, n_groups: int, gamma: int, seed: int, row_offset: int = 0, stream=None):
+    """Returns (n_accept, log_ratio, accept_mask)."""
+    R = n_groups * gamma
+    K, D = _mix(mix_p, R)
+    assert _mix(mix_q, R) == (K, D)
+    assert x.is_cuda and x.is_contiguous() and x.dtype == torch.float32 and tuple(x.shape) == (R, D)
+    dev = x.device
+    n_accept = torch.empty(n_groups, dtype=torch.int32, device=dev)
+    log_ratio = torch.empty(R, dtype=torch.float32, device=dev)
+    mask = torch.empty(R, dtype=torch.uint8, device=dev)
+    _check(_lib.csd_gmm_verify(_ptr(x), *[_ptr(t) for t in mix_p], *[_ptr(t) for t in mix_q], n_groups, gamma, K, D, seed,
+                               row_offset, _ptr(n_accept), _ptr(log_ratio), _ptr(mask), _stream(stream)))
+    return n_accept, log_ratio, mask
+
+
+def csd_gmm_resample(x: torch.Tensor, n_accept: torch.Tensor, mix_p, mix_q, n_groups: int, gamma: int, seed: int,
+                     row_offset: int = 0, max_trips: int = 1024, stream=None):
+    """Returns (tokens [G, gamma+1, D], n_out, trips, flags)."""
+    R = n_groups * gamma
+    K, D = _mix(mix_p, R)
+    assert _mix(mix_q, R) == (K, D)
+    assert x.is_cuda and x.is_contiguous() and x.dtype == torch.float32 and tuple(x.shape) == (R, D)
+    assert n_accept.is_cuda and n_accept.dtype == torch.int32 and n_accept.numel() == n_groups
+    dev = x.device
+    tokens = torch.empty((n_groups, gamma + 1, D), dtype=torch.float32, device=dev)
+    n_out = torch.empty(n_groups, dtype=torch.int32, device=dev)
+    trips = torch.empty(n_groups, dtype=torch.int32, device=dev)
+    flags = torch.empty(n_groups, dtype=torch.int32, device=dev)
+    _check(_lib.csd_gmm_resample(_ptr(x), _ptr(n_accept), *[_ptr(t) for t in mix_p], *[_ptr(t) for t in mix_q], n_groups,
+                                 gamma, K, D, seed, row_offset, max_trips, _ptr(tokens), _ptr(n_out), _ptr(trips),
+                                 _ptr(flags), _stream(stream)))
     return tokens, n_out, trips, flags
 
 

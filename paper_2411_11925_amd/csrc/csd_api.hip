@@ -802,6 +802,59 @@ int csd_append_bonus(float* tokens, int32_t* n_out, const int32_t* n_accept, con
     return CSD_OK;
 }
 
+namespace {
+int check_gmm(const char* who, int64_t n, int gamma, int K, int D) {
+    if (n < 0 || gamma < 1 || gamma > 64) return fail(CSD_EINVAL, "%s: n >= 0 and 1 <= gamma <= 64 required", who);
+    if (K < 1 || K > 64) return fail(CSD_EINVAL, "%s: 1 <= n_components <= 64 required", who);
+    if (!(D == 4 || D == 8 || D == 16)) return fail(CSD_EINVAL, "%s: token_dim must be 4, 8 or 16", who);
+    if (n > (int64_t)1 << 30) return fail(CSD_EINVAL, "%s: too many rows", who);
+    return CSD_OK;
+}
+}  // namespace
+
+int csd_gmm_draft_sample(const float* pi_q, const float* mu_q, const float* logvar_q, int64_t n_rows,
+                         int32_t n_components, int32_t token_dim, uint64_t seed, uint64_t row_offset, float* x,
+                         void* hip_stream) {
+    int rc = check_gmm("csd_gmm_draft_sample", n_rows, 1, n_components, token_dim);
+    if (rc != CSD_OK) return rc;
+    if (n_rows == 0) return CSD_OK;
+    if (!pi_q || !mu_q || !logvar_q || !x) return fail(CSD_EINVAL, "csd_gmm_draft_sample: NULL buffer");
+    HIP_TRY(launch_gmm_draft_sample(pi_q, mu_q, logvar_q, n_rows, n_components, token_dim, seed, row_offset, x,
+                                    (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
+int csd_gmm_verify(const float* x, const float* pi_p, const float* mu_p, const float* logvar_p, const float* pi_q,
+                   const float* mu_q, const float* logvar_q, int64_t n_groups, int32_t gamma, int32_t n_components,
+                   int32_t token_dim, uint64_t seed, uint64_t row_offset, int32_t* n_accept, float* log_ratio,
+                   uint8_t* accept_mask, void* hip_stream) {
+    int rc = check_gmm("csd_gmm_verify", n_groups, gamma, n_components, token_dim);
+    if (rc != CSD_OK) return rc;
+    if (n_groups == 0) return CSD_OK;
+    if (!x || !pi_p || !mu_p || !logvar_p || !pi_q || !mu_q || !logvar_q || !n_accept)
+        return fail(CSD_EINVAL, "csd_gmm_verify: NULL buffer");
+    HIP_TRY(launch_gmm_verify(x, pi_p, mu_p, logvar_p, pi_q, mu_q, logvar_q, n_groups, gamma, n_components, token_dim,
+                              seed, row_offset, n_accept, log_ratio, accept_mask, (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
+int csd_gmm_resample(const float* x, const int32_t* n_accept, const float* pi_p, const float* mu_p,
+                     const float* logvar_p, const float* pi_q, const float* mu_q, const float* logvar_q,
+                     int64_t n_groups, int32_t gamma, int32_t n_components, int32_t token_dim, uint64_t seed,
+                     uint64_t row_offset, int32_t max_trips, float* tokens, int32_t* n_out, int32_t* trips,
+                     uint32_t* flags, void* hip_stream) {
+    int rc = check_gmm("csd_gmm_resample", n_groups, gamma, n_components, token_dim);
+    if (rc != CSD_OK) return rc;
+    if (max_trips < 1 || max_trips > 65534) return fail(CSD_EINVAL, "csd_gmm_resample: 1 <= max_trips <= 65534 required");
+    if (n_groups == 0) return CSD_OK;
+    if (!x || !n_accept || !pi_p || !mu_p || !logvar_p || !pi_q || !mu_q || !logvar_q || !tokens || !n_out)
+        return fail(CSD_EINVAL, "csd_gmm_resample: NULL buffer");
+    HIP_TRY(launch_gmm_resample(x, n_accept, pi_p, mu_p, logvar_p, pi_q, mu_q, logvar_q, n_groups, gamma, n_components,
+                                token_dim, seed, row_offset, max_trips, tokens, n_out, trips, flags,
+                                (hipStream_t)hip_stream));
+    return CSD_OK;
+}
+
 int csd_head_eval(const csd_head_t* head, const float* x, const float* z, int32_t t, int64_t n_rows, float* out,
                   void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!head) return fail(CSD_EINVAL, "csd_head_eval: NULL head");

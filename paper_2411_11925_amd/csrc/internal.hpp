@@ -167,6 +167,16 @@ hipError_t launch_verify(const float* summary, int64_t G, int gamma, int D, uint
 hipError_t launch_resample(const float* summary, const int32_t* n_accept, int64_t G, int gamma, int D,
                            uint64_t seed, uint64_t row_offset, float tau, int max_trips,
                            float* tokens, int32_t* n_out, int32_t* trips, uint32_t* flags, hipStream_t st);
+// mixture-of-Gaussians heads (gmm.hip): pi [R,K], mu / logvar [R,K,D]
+hipError_t launch_gmm_draft_sample(const float* pi, const float* mu, const float* lv, int64_t R, int K, int D,
+                                   uint64_t seed, uint64_t row_offset, float* x, hipStream_t st);
+hipError_t launch_gmm_verify(const float* x, const float* pi_p, const float* mu_p, const float* lv_p, const float* pi_q,
+                             const float* mu_q, const float* lv_q, int64_t G, int gamma, int K, int D, uint64_t seed,
+                             uint64_t row_offset, int32_t* n_accept, float* log_ratio, uint8_t* mask, hipStream_t st);
+hipError_t launch_gmm_resample(const float* x, const int32_t* n_accept, const float* pi_p, const float* mu_p,
+                               const float* lv_p, const float* pi_q, const float* mu_q, const float* lv_q, int64_t G,
+                               int gamma, int K, int D, uint64_t seed, uint64_t row_offset, int max_trips, float* tokens,
+                               int32_t* n_out, int32_t* trips, uint32_t* flags, hipStream_t st);
 hipError_t launch_rng_normals(uint64_t seed, uint64_t row_offset, int64_t R, int slot, int stream_id, int n_cols,
                               float* out, hipStream_t st);
 hipError_t launch_rng_uniforms(uint64_t seed, uint64_t row_offset, int64_t R, int slot, int stream_id,

@@ -184,3 +184,30 @@ WORKLOADS = {
     "reject": Workload("reject", HeadShape(16, 768, 1024, 6), HeadShape(16, 768, 768, 6),
                        100, 256, 8, 256, 0.5, 0.002, 1.0, "bf16", _SEED + 5),
 }
+
+
+def mixture_pair(n_rows: int, n_components: int, token_dim: int, seed: int, shift: float = 0.3,
+                 row_offset: int = 0):
+    """Parameters of a target and a draft mixture-of-Gaussians head for rows
+    [row_offset, row_offset + n_rows): ((pi_p, mu_p, logvar_p), (pi_q, mu_q, logvar_q)), fp32,
+    pi [n, K] unnormalised positive weights, mu / logvar [n, K, D].  The draft is the target
+    with its means moved by `shift` standard deviations, its variances widened or narrowed
+    by up to 35 % and its weights re-drawn around the target's - the kind of disagreement
+    a smaller model has with a larger one.  Rows are drawn in blocks of 64 keyed by the
+    block index, like the conditioning vectors."""
+    assert row_offset % 64 == 0
+    K, D = n_components, token_dim
+    out = [np.empty((n_rows, K), np.float32), np.empty((n_rows, K, D), np.float32), np.empty((n_rows, K, D), np.float32),
+           np.empty((n_rows, K), np.float32), np.empty((n_rows, K, D), np.float32), np.empty((n_rows, K, D), np.float32)]
+    for b0 in range(0, n_rows, 64):
+        n = min(64, n_rows - b0)
+        g = _rng(seed * 1000003 + (row_offset + b0) // 64, 23)
+        pi_p = g.uniform(0.2, 1.0, size=(64, K))
+        mu_p = g.normal(size=(64, K, D))
+        lv_p = g.uniform(-2.5, -0.5, size=(64, K, D))
+        pi_q = pi_p * g.uniform(0.6, 1.4, size=(64, K))
+        mu_q = mu_p + shift * np.exp(0.5 * lv_p) * g.normal(size=(64, K, D))
+        lv_q = lv_p + g.uniform(-0.3, 0.3, size=(64, K, D))
+        for dst, src in zip(out, (pi_p, mu_p, lv_p, pi_q, mu_q, lv_q)):
+            dst[b0:b0 + n] = src[:n]
+    return tuple(out[:3]), tuple(out[3:])

@@ -68,6 +68,9 @@ def test_argument_errors_without_device_work(B):
     assert lib.csd_denoise_target(None, None, None, 1, 1, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
     assert lib.csd_sample(None, None, 1, 0, 0, 0, 1.0, None, None, 0, None) == B.CSD_EINVAL
     assert lib.csd_set_guidance(None, 1, 1.0) == B.CSD_EINVAL
+    assert lib.csd_gmm_draft_sample(None, None, None, 4, 2, 16, 0, 0, None, None) == B.CSD_EINVAL
+    assert lib.csd_gmm_verify(None, None, None, None, None, None, None, 4, 2, 2, 16, 0, 0, None, None, None, None) == B.CSD_EINVAL
+    assert lib.csd_gmm_resample(None, None, None, None, None, None, None, None, 4, 2, 2, 16, 0, 0, 8, None, None, None, None, None) == B.CSD_EINVAL
     assert lib.csd_append_bonus(None, None, None, None, 4, 0, 16, None) == B.CSD_EINVAL
     assert lib.csd_append_bonus(None, None, None, None, 4, 4, 5, None) == B.CSD_EINVAL
     assert lib.csd_append_bonus(None, None, None, None, 4, 4, 16, None) == B.CSD_EINVAL      # NULL buffers
