@@ -75,33 +75,69 @@ __global__ __launch_bounds__(256) void k_gmm_draft_sample(const float* __restric
 
 struct Mix { const float* pi; const float* mu; const float* lv; };
 
-// one wave per group
+// The accept test reads both mixtures of every row once and is bound by HBM, so its lanes are
+// laid out for wide loads: a team of L lanes takes one row, L/(D/4) components at a time, each
+// lane 4 consecutive coordinates of one component (one 16-byte load of mu and of logvar).  A
+// component's exponent is summed over its D/4 lanes, the log-sum-exp over the team.
+// L = the power of two >= K*D/4, at most 16; 64/L rows of the group per pass.  One wave per group.
+template <int D>
+__device__ __forceinline__ float team_logpdf(const float4 x4, const float* __restrict__ pi, const float* __restrict__ mu,
+                                             const float* __restrict__ lv, int K, int L, int t) {
+    constexpr int PD = D / 4;                    // lanes per component
+    const int kc = t / PD, d0 = (t % PD) * 4, CK = L / PD;
+    float total = 0.f;
+    for (int k = 0; k < K; ++k) total += pi[k];
+    float m = -INFINITY, s = 0.f;
+    for (int k0 = 0; k0 < K; k0 += CK) {
+        const int k = k0 + kc;
+        const bool valid = k < K;
+        const int kk = valid ? k : K - 1;
+        const float4 m4 = *reinterpret_cast<const float4*>(mu + kk * D + d0);
+        const float4 l4 = *reinterpret_cast<const float4*>(lv + kk * D + d0);
+        const float w = pi[kk];
+        const float z0 = x4.x - m4.x, z1 = x4.y - m4.y, z2 = x4.z - m4.z, z3 = x4.w - m4.w;
+        float c = fmaf(z0 * z0, expf(-l4.x), l4.x) + fmaf(z1 * z1, expf(-l4.y), l4.y) +
+                  fmaf(z2 * z2, expf(-l4.z), l4.z) + fmaf(z3 * z3, expf(-l4.w), l4.w);
+#pragma unroll
+        for (int o = PD / 2; o >= 1; o >>= 1) c += __shfl_xor(c, o, 64);
+        const float a = (valid && w > 0.f) ? fmaf(-0.5f, c, logf(w)) : -INFINITY;
+        float mc = a;                            // maximum over the team's components of this chunk
+        for (int o = L / 2; o >= 1; o >>= 1) mc = fmaxf(mc, __shfl_xor(mc, o, 64));
+        if (mc > -INFINITY) {                    // (uniform over the team)
+            float e = (t % PD == 0 && a > -INFINITY) ? expf(a - mc) : 0.f;    // one lane per component adds
+            for (int o = L / 2; o >= 1; o >>= 1) e += __shfl_xor(e, o, 64);
+            if (mc > m) { s = s * expf(m - mc) + e; m = mc; }
+            else s += e * expf(mc - m);
+        }
+    }
+    return m + logf(s) - logf(total);
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void k_gmm_verify(const float* __restrict__ x, Mix p, Mix q, int64_t G, int gamma, int K,
-                                                    uint64_t seed, uint64_t row_offset, int32_t* __restrict__ n_accept,
-                                                    float* __restrict__ log_ratio, uint8_t* __restrict__ mask) {
-    constexpr int S = 64 / D;
+                                                    int L, uint64_t seed, uint64_t row_offset,
+                                                    int32_t* __restrict__ n_accept, float* __restrict__ log_ratio,
+                                                    uint8_t* __restrict__ mask) {
     const int lane = threadIdx.x & 63;
     const int64_t g = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     if (g >= G) return;
-    const int seg = lane / D, d = lane % D;
+    const int RPW = 64 / L, team = lane / L, t = lane % L;
     int first_reject = gamma;
-    for (int i0 = 0; i0 < gamma; i0 += S) {
-        const int i = i0 + seg;
-        // rows past the group's end are evaluated on the group's last row (the segment sums
-        // need all lanes) and never reject
+    for (int i0 = 0; i0 < gamma; i0 += RPW) {
+        const int i = i0 + team;
+        // teams past the group's end evaluate its last row (the shuffles need all lanes) and never reject
         const int64_t r = g * gamma + (i < gamma ? i : gamma - 1);
-        const float xv = x[r * D + d];
-        const float ell = mix_logpdf<D>(xv, p.pi + r * K, p.mu + r * K * D, p.lv + r * K * D, K, d) -
-                          mix_logpdf<D>(xv, q.pi + r * K, q.mu + r * K * D, q.lv + r * K * D, K, d);
+        const float4 x4 = *reinterpret_cast<const float4*>(x + r * D + (t % (D / 4)) * 4);
+        const float ell = team_logpdf<D>(x4, p.pi + r * K, p.mu + r * K * D, p.lv + r * K * D, K, L, t) -
+                          team_logpdf<D>(x4, q.pi + r * K, q.mu + r * K * D, q.lv + r * K * D, K, L, t);
         const float u = uniform_at(seed, row_offset + (uint64_t)r, 0u, CSD_STREAM_ACCEPT_U);
         const bool accept = (i >= gamma) || (logf(u) <= ell);            // NaN compares false: reject
-        if (i < gamma && d == 0) {
+        if (i < gamma && t == 0) {
             if (log_ratio) log_ratio[r] = ell;
             if (mask) mask[r] = accept ? 1 : 0;
         }
-        const unsigned long long rej = __ballot(!accept);
-        if (rej != 0ull && first_reject == gamma) first_reject = i0 + (__ffsll((long long)rej) - 1) / D;
+        const unsigned long long rej = __ballot(!accept);                // L equal bits per team
+        if (rej != 0ull && first_reject == gamma) first_reject = i0 + (__ffsll((long long)rej) - 1) / L;
     }
     if (lane == 0) n_accept[g] = first_reject;
 }
@@ -191,7 +227,11 @@ hipError_t launch_gmm_verify(const float* x, const float* pi_p, const float* mu_
     if (G == 0) return hipSuccess;
     const dim3 grid((unsigned)((G + 3) / 4));
     const Mix p{pi_p, mu_p, lv_p}, q{pi_q, mu_q, lv_q};
-    CSD_BY_D(k_gmm_verify, grid, x, p, q, G, gamma, K, seed, row_offset, n_accept, log_ratio, mask)
+    // lanes of a row's team: the power of two >= K*D/4, at most 16, so that at least four rows are in
+    // flight per wave (one row per wave with 64 lanes was measured: 2.5 against 3.7 TB/s at K = 16)
+    int L = D / 4;
+    while (L < 16 && L < K * (D / 4)) L *= 2;
+    CSD_BY_D(k_gmm_verify, grid, x, p, q, G, gamma, K, L, seed, row_offset, n_accept, log_ratio, mask)
     return hipGetLastError();
 }
 
