@@ -60,6 +60,7 @@ __device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0x
 template <int BM, int BN, int WM, int WN, int BK, int NST, int EPI, bool OUT_F32, bool PIPE = false>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     constexpr int NW = WM * WN;
+    constexpr bool WIDE_EPI = (NW == 4 && BM == 256);     // measured per tile form
     constexpr int TM = BM / WM, TN = BN / WN;          // per-wave tile
     constexpr int FM = TM / 32, FN = TN / 32;          // 32x32 blocks per wave
     constexpr int ROW_B = BK * 2;                      // bytes per LDS row
@@ -278,9 +279,12 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
     // every pass, which also waits for the previous pass's store: the passes would run
     // one store round trip at a time.
     const int n_ep = n0 + wn * TN + (rd_c < NCH ? rd_c : 0) * 4;
-    float4 bb = *reinterpret_cast<const float4*>(p.bias + n_ep);
-    if (blockIdx.y != 0) bb = make_float4(0.f, 0.f, 0.f, 0.f);       // the bias goes into the first K range only
-    asm volatile("" : "+v"(bb.x), "+v"(bb.y), "+v"(bb.z), "+v"(bb.w));
+    float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto load_bb = [&]() {
+        bb = *reinterpret_cast<const float4*>(p.bias + n_ep);
+        if (blockIdx.y != 0) bb = make_float4(0.f, 0.f, 0.f, 0.f);   // the bias goes into the first K range only
+        asm volatile("" : "+v"(bb.x), "+v"(bb.y), "+v"(bb.z), "+v"(bb.w));
+    };
     // Tiles that lie wholly inside M take the copy of the code without row guards, where the
     // compiler is free to batch the LDS reads and stores of a slab.
     auto emit = [&](auto guard_c) {
@@ -323,7 +327,51 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_bf16(Params p) {
             }
         }
     };
-    if (m0 + BM <= p.M) emit(std::false_type{}); else emit(std::true_type{});
+    // bf16 output (plain or SiLU epilogue) with an even number of chunks per row: the same staging, but a
+    // lane takes two neighbouring chunks and stores 16 bytes (8 features), half as many store instructions
+    auto emit_wide = [&](auto guard_c) {
+        constexpr bool GUARD = decltype(guard_c)::value;
+        constexpr int LPR2 = LPR / 2, RPP2 = 64 / LPR2, NCH2 = NCH / 2;
+        const int row0 = lane / LPR2, c2 = lane % LPR2;
+        const int n8 = n0 + wn * TN + (c2 < NCH2 ? c2 : 0) * 8;
+        float4 b0 = *reinterpret_cast<const float4*>(p.bias + n8), b1 = *reinterpret_cast<const float4*>(p.bias + n8 + 4);
+        asm volatile("" : "+v"(b0.x), "+v"(b0.y), "+v"(b0.z), "+v"(b0.w), "+v"(b1.x), "+v"(b1.y), "+v"(b1.z), "+v"(b1.w));
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c = j * 8 + q * 2 + khalf;
+                    *reinterpret_cast<float4*>(stg + l32 * TN + ((c ^ stg_swz(l32)) << 2)) =
+                        make_float4(acc[i][j][4 * q + 0], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                }
+            if (c2 >= NCH2) continue;
+#pragma unroll
+            for (int pass = 0; pass < 32 / RPP2; ++pass) {
+                const int row = pass * RPP2 + row0;
+                const float4 a0 = *reinterpret_cast<const float4*>(stg + row * TN + (((2 * c2) ^ stg_swz(row)) << 2));
+                const float4 a1 = *reinterpret_cast<const float4*>(stg + row * TN + (((2 * c2 + 1) ^ stg_swz(row)) << 2));
+                const int64_t m = m0 + wm * TM + i * 32 + row;
+                if (GUARD && m >= p.M) continue;
+                float v0 = a0.x + b0.x, v1 = a0.y + b0.y, v2 = a0.z + b0.z, v3 = a0.w + b0.w;
+                float v4 = a1.x + b1.x, v5 = a1.y + b1.y, v6 = a1.z + b1.z, v7 = a1.w + b1.w;
+                if (EPI == EPI_BIAS_SILU) {
+                    v0 = silu_fast(v0); v1 = silu_fast(v1); v2 = silu_fast(v2); v3 = silu_fast(v3);
+                    v4 = silu_fast(v4); v5 = silu_fast(v5); v6 = silu_fast(v6); v7 = silu_fast(v7);
+                }
+                *reinterpret_cast<uint4*>((bf16_t*)p.C + m * p.ldc + n8) =
+                    make_uint4(pack_bf16x2(v0, v1), pack_bf16x2(v2, v3), pack_bf16x2(v4, v5), pack_bf16x2(v6, v7));
+            }
+        }
+    };
+    if constexpr (!OUT_F32 && EPI != EPI_GATE_RES && NCH % 2 == 0 && LPR % 2 == 0 && WIDE_EPI) {
+        // (the launcher sends bf16 outputs whose rows do not start on 16-byte boundaries to another tile form)
+        if (m0 + BM <= p.M) emit_wide(std::false_type{}); else emit_wide(std::true_type{});
+    } else {
+        load_bb();
+        if (m0 + BM <= p.M) emit(std::false_type{}); else emit(std::true_type{});
+    }
     if (p.ts && (threadIdx.x & 63) == 0) atomicMax(p.ts + 1, (unsigned long long)__builtin_amdgcn_s_memrealtime());
 }
 
@@ -400,6 +448,7 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t st) {
         else variant = 3;
     }
     if (g.k_splits > 1) variant = 3;
+    if (variant == 12 && !g.c_is_f32 && g.epi != EPI_GATE_RES && g.ldc % 8 != 0) variant = 9;   // 16-byte stores of the 4-wave form
     if ((variant == 1 || variant == 9 || variant == 12) && g.N % 256 != 0) variant = (g.N % 192 == 0) ? 8 : 3;
     if (variant == 8 && g.N % 192 != 0) variant = 3;
     switch (variant) {
